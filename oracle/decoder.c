@@ -1,0 +1,381 @@
+/*
+ * CPU oracle (test infrastructure): the speculative Jacobi decoding loop.
+ *
+ * Sec. 4.1 of the paper, in its order:
+ *   Step 1  the window holds the drafts that were not accepted plus newly
+ *           initialised ones; each draft carries the distribution it was
+ *           predicted with at the previous iteration (its reference q);
+ *   Step 2  one causal forward over the window gives the new distributions p;
+ *   Step 3  drafts are accepted left to right with probability min(1, p/q)
+ *           (Eq. 2); accepted tokens are final;
+ *   Step 4  the first unaccepted position is redrawn from the residual
+ *           normalise(max(0, p - q)) (Eq. 3); every later draft is kept if its
+ *           confidence p/q exceeds tau (Eq. 4-5) and otherwise redrawn from p;
+ *           tau = +inf is the rule without reuse (Eq. 6).
+ *
+ * Readings where the paper is silent (listed in the design notes):
+ *   - the first window input is the last final token (anchor), so output row k
+ *     is the distribution of the position after input k, and the draft in slot
+ *     k + 1 is verified against row k;
+ *   - the token drawn at the first unaccepted position is final at once; if
+ *     every draft is accepted a token is drawn from the last row instead;
+ *   - a draft that never had a row (freshly initialised, drawn uniformly over
+ *     the sampled range) has the uniform distribution as its reference;
+ *   - the last row of a rejecting step has no draft: its slot enters the next
+ *     window drawn from that row;
+ *   - near the end of the image the window shrinks to the tokens remaining.
+ *
+ * Randomness: Philox4x32-10, key = seed, counter = (step, row, sequence, 0).
+ * Word 0 is the acceptance uniform of the draft verified at that row, words
+ * 1-2 the 64-bit uniform of the one draw made at that row, word 3 a fresh
+ * uniform draft.  step = 0 is the initial window, steps count from 1.
+ */
+#include "oracle_internal.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { OK = 0, EINVAL_ = -1, ENOMEM_ = -2, ESTATE_ = -3, ECAPACITY_ = -5 };
+
+typedef struct {
+    int32_t cond_len, uncond_len, n_image;
+    int32_t n_img; /* image tokens final so far */
+    int32_t *out;  /* [n_image] */
+    int32_t anchor[2];
+    int32_t *tok;     /* [L] window tokens, slot 0 unused (anchor above) */
+    int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform */
+    float *ref_e;     /* [L][V_s] rows of the previous step */
+    uint64_t *ref_Z;  /* [L] */
+    oracle_cache *cache[2];
+    int32_t done;
+} seq_state;
+
+struct oracle_ctx {
+    oracle_model_desc md;
+    oracle_weights w;
+    oracle_sampling sp;
+    int32_t max_seqs, n_seqs, Vs, L;
+    uint32_t step;
+    int prefilled;
+    seq_state *seq;
+    float *logits;  /* [max_seqs][2][L][V_s] of the last step */
+    float *new_e;   /* [L][V_s] scratch */
+    uint64_t *new_Z;
+};
+
+int oracle_set_num_threads(int32_t n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
+static void seq_release(seq_state *s) {
+    free(s->out); free(s->tok); free(s->ref_row); free(s->ref_e); free(s->ref_Z);
+    oracle_cache_free(s->cache[0]);
+    oracle_cache_free(s->cache[1]);
+    memset(s, 0, sizeof *s);
+}
+
+int oracle_create(const oracle_model_desc *md, const oracle_weights *w, const oracle_sampling *sp,
+                  int32_t max_seqs, oracle_ctx **out) {
+    if (!md || !w || !sp || !out || max_seqs < 1) return EINVAL_;
+    if (md->window < 1 || md->n_layers < 1 || md->n_heads < 1 || md->n_kv_heads < 1) return EINVAL_;
+    if (md->d_model % md->n_heads || md->n_heads % md->n_kv_heads || (md->d_model / md->n_heads) % 2) return EINVAL_;
+    if (md->sample_lo < 0 || md->sample_hi > md->vocab || md->sample_hi <= md->sample_lo) return EINVAL_;
+    if (sp->top_k < 1 || !(sp->temperature > 0.0f)) return EINVAL_;
+    oracle_ctx *c = (oracle_ctx *)calloc(1, sizeof *c);
+    if (!c) return ENOMEM_;
+    c->md = *md; c->w = *w; c->sp = *sp;
+    c->max_seqs = max_seqs;
+    c->Vs = md->sample_hi - md->sample_lo;
+    c->L = md->window;
+    c->seq = (seq_state *)calloc((size_t)max_seqs, sizeof(seq_state));
+    c->logits = (float *)calloc((size_t)max_seqs * 2 * c->L * c->Vs, sizeof(float));
+    c->new_e = (float *)calloc((size_t)c->L * c->Vs, sizeof(float));
+    c->new_Z = (uint64_t *)calloc((size_t)c->L, sizeof(uint64_t));
+    if (!c->seq || !c->logits || !c->new_e || !c->new_Z) { oracle_destroy(c); return ENOMEM_; }
+    *out = c;
+    return OK;
+}
+
+void oracle_destroy(oracle_ctx *c) {
+    if (!c) return;
+    if (c->seq) for (int s = 0; s < c->max_seqs; ++s) seq_release(&c->seq[s]);
+    free(c->seq); free(c->logits); free(c->new_e); free(c->new_Z);
+    free(c);
+}
+
+static void philox(const oracle_ctx *c, uint32_t step, uint32_t row, uint32_t seq, uint32_t out[4]) {
+    uint32_t ctr[4] = {step, row, seq, 0};
+    uint32_t key[2] = {(uint32_t)c->sp.seed, (uint32_t)(c->sp.seed >> 32)};
+    oracle_philox4x32_10(ctr, key, out);
+}
+
+static int32_t fresh_token(const oracle_ctx *c, uint32_t word3) {
+    return c->md.sample_lo + (int32_t)(((uint64_t)word3 * (uint64_t)c->Vs) >> 32);
+}
+
+int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, const int32_t *cond_len,
+                   const int32_t *const *uncond_ids, const int32_t *uncond_len,
+                   const int32_t *n_image_tokens) {
+    if (!c || !cond_ids || !cond_len || !uncond_ids || !uncond_len || !n_image_tokens) return EINVAL_;
+    if (n_seqs < 1) return EINVAL_;
+    if (n_seqs > c->max_seqs) return ECAPACITY_;
+    for (int s = 0; s < n_seqs; ++s) {
+        if (cond_len[s] < 1 || uncond_len[s] < 1 || n_image_tokens[s] < 1) return EINVAL_;
+        if (cond_len[s] + n_image_tokens[s] > c->md.max_ctx) return ECAPACITY_;
+        if (uncond_len[s] + n_image_tokens[s] > c->md.max_ctx) return ECAPACITY_;
+        for (int i = 0; i < cond_len[s]; ++i)
+            if (cond_ids[s][i] < 0 || cond_ids[s][i] >= c->md.vocab) return EINVAL_;
+        for (int i = 0; i < uncond_len[s]; ++i)
+            if (uncond_ids[s][i] < 0 || uncond_ids[s][i] >= c->md.vocab) return EINVAL_;
+    }
+    for (int s = 0; s < c->max_seqs; ++s) seq_release(&c->seq[s]);
+    c->n_seqs = n_seqs;
+    c->step = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        seq_state *q = &c->seq[s];
+        q->cond_len = cond_len[s]; q->uncond_len = uncond_len[s]; q->n_image = n_image_tokens[s];
+        q->out = (int32_t *)calloc((size_t)q->n_image, sizeof(int32_t));
+        q->tok = (int32_t *)calloc((size_t)c->L, sizeof(int32_t));
+        q->ref_row = (int32_t *)calloc((size_t)c->L, sizeof(int32_t));
+        q->ref_e = (float *)calloc((size_t)c->L * c->Vs, sizeof(float));
+        q->ref_Z = (uint64_t *)calloc((size_t)c->L, sizeof(uint64_t));
+        q->cache[0] = oracle_cache_new(&c->md);
+        q->cache[1] = oracle_cache_new(&c->md);
+        if (!q->out || !q->tok || !q->ref_row || !q->ref_e || !q->ref_Z || !q->cache[0] || !q->cache[1]) return ENOMEM_;
+        /* all prompt tokens but the last go into the cache; the last one is
+         * the first window input */
+        const int32_t *ids[2] = {cond_ids[s], uncond_ids[s]};
+        const int32_t len[2] = {cond_len[s], uncond_len[s]};
+        for (int b = 0; b < 2; ++b) {
+            if (len[b] > 1) {
+                int rc = oracle_forward(&c->md, &c->w, q->cache[b], ids[b], len[b] - 1, NULL);
+                if (rc) return rc;
+            }
+            q->cache[b]->len = len[b] - 1;
+            q->anchor[b] = ids[b][len[b] - 1];
+        }
+        int32_t Le = q->n_image < c->L ? q->n_image : c->L;
+        for (int k = 1; k < Le; ++k) {
+            uint32_t r[4];
+            philox(c, 0, (uint32_t)k, (uint32_t)s, r);
+            q->tok[k] = fresh_token(c, r[3]);
+            q->ref_row[k] = -1;
+        }
+    }
+    c->prefilled = 1;
+    return OK;
+}
+
+/* probability weight of token id `tok` under reference of slot k */
+static void ref_of(const oracle_ctx *c, const seq_state *q, int k, int32_t tok, uint64_t *w, uint64_t *Z) {
+    if (q->ref_row[k] < 0) { *w = 1; *Z = (uint64_t)c->Vs; return; }
+    const float *row = q->ref_e + (size_t)q->ref_row[k] * c->Vs;
+    *w = oracle_weight_of(row[tok - c->md.sample_lo]);
+    *Z = q->ref_Z[q->ref_row[k]];
+}
+
+/* Steps 3 and 4 for one sequence, given this step's rows (new_e, new_Z). */
+static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
+    seq_state *q = &c->seq[s];
+    const int Vs = c->Vs, lo = c->md.sample_lo;
+    const uint32_t step = c->step;
+    uint32_t r[4];
+
+    /* Step 3: leading run of accepted drafts; draft in slot k against row k-1 */
+    int a = 0;
+    for (int k = 1; k < Le; ++k) {
+        philox(c, step, (uint32_t)(k - 1), (uint32_t)s, r);
+        int32_t x = q->tok[k];
+        uint64_t wq, Zq;
+        ref_of(c, q, k, x, &wq, &Zq);
+        uint64_t wp = oracle_weight_of(c->new_e[(size_t)(k - 1) * Vs + (x - lo)]);
+        if (!oracle_accept(r[0], wp, c->new_Z[k - 1], wq, Zq)) break;
+        a += 1;
+    }
+    const int rejected = a < Le - 1;
+
+    /* Step 4, first unaccepted position: residual draw (or a plain draw from
+     * the last row when nothing was rejected) */
+    philox(c, step, (uint32_t)a, (uint32_t)s, r);
+    uint64_t u64 = ((uint64_t)r[1] << 32) | r[2];
+    const float *pa = c->new_e + (size_t)a * Vs;
+    int32_t y;
+    if (rejected) {
+        int rr = q->ref_row[a + 1];
+        const float *qe = rr < 0 ? NULL : q->ref_e + (size_t)rr * Vs;
+        y = lo + oracle_draw_residual(pa, c->new_Z[a], qe, rr < 0 ? 0 : q->ref_Z[rr], Vs, u64);
+    } else {
+        y = lo + oracle_draw(pa, c->new_Z[a], Vs, u64);
+    }
+
+    for (int k = 1; k <= a; ++k) q->out[q->n_img + k - 1] = q->tok[k];
+    q->out[q->n_img + a] = y;
+    q->n_img += a + 1;
+    q->cache[0]->len += a + 1;
+    q->cache[1]->len += a + 1;
+
+    res->n_accepted = a;
+    res->n_finalized = a + 1;
+    res->reject_index = rejected ? a + 1 : -1;
+
+    const int remaining = q->n_image - q->n_img;
+    if (remaining == 0) {
+        q->done = 1;
+        res->done = 1;
+        return;
+    }
+    res->done = 0;
+
+    /* next window: slot k' holds what was slot k = k' + a + 1 */
+    const int Le2 = remaining < c->L ? remaining : c->L;
+    int32_t *tok2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)c->L);
+    int32_t *ref2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)c->L);
+    for (int k2 = 1; k2 < Le2; ++k2) {
+        int k = k2 + a + 1;
+        if (k <= Le - 1) {
+            /* Eq. 4-5 at a later position: draft of slot k, row k-1 */
+            int32_t x = q->tok[k];
+            uint64_t wq, Zq;
+            ref_of(c, q, k, x, &wq, &Zq);
+            const float *prow = c->new_e + (size_t)(k - 1) * Vs;
+            if (oracle_keep(c->sp.reuse_tau, oracle_weight_of(prow[x - lo]), c->new_Z[k - 1], wq, Zq)) {
+                tok2[k2] = x;
+            } else {
+                philox(c, step, (uint32_t)(k - 1), (uint32_t)s, r);
+                tok2[k2] = lo + oracle_draw(prow, c->new_Z[k - 1], Vs, ((uint64_t)r[1] << 32) | r[2]);
+            }
+            ref2[k2] = k - 1;
+        } else if (k == Le) {
+            /* the last row had no draft: its slot is drawn from that row */
+            philox(c, step, (uint32_t)(Le - 1), (uint32_t)s, r);
+            tok2[k2] = lo + oracle_draw(c->new_e + (size_t)(Le - 1) * Vs, c->new_Z[Le - 1], Vs,
+                                        ((uint64_t)r[1] << 32) | r[2]);
+            ref2[k2] = Le - 1;
+        } else {
+            philox(c, step, (uint32_t)k, (uint32_t)s, r);
+            tok2[k2] = fresh_token(c, r[3]);
+            ref2[k2] = -1;
+        }
+    }
+    q->anchor[0] = q->anchor[1] = y;
+    for (int k2 = 1; k2 < Le2; ++k2) { q->tok[k2] = tok2[k2]; q->ref_row[k2] = ref2[k2]; }
+    for (int k2 = Le2; k2 < c->L; ++k2) { q->tok[k2] = 0; q->ref_row[k2] = -1; }
+    memcpy(q->ref_e, c->new_e, sizeof(float) * (size_t)Le * Vs);
+    memcpy(q->ref_Z, c->new_Z, sizeof(uint64_t) * (size_t)Le);
+    free(ref2);
+    free(tok2);
+}
+
+static int step_impl(oracle_ctx *c, const float *given_logits, oracle_step_result *out) {
+    if (!c || !out) return EINVAL_;
+    if (!c->prefilled) return ESTATE_;
+    const int L = c->L, Vs = c->Vs;
+    c->step += 1;
+    int32_t *win = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
+    for (int s = 0; s < c->n_seqs; ++s) {
+        seq_state *q = &c->seq[s];
+        oracle_step_result *res = &out[s];
+        if (q->done) {
+            res->n_accepted = 0; res->n_finalized = 0; res->reject_index = -1; res->done = 1;
+            continue;
+        }
+        const int remaining = q->n_image - q->n_img;
+        const int Le = remaining < L ? remaining : L;
+        float *lg = c->logits + (size_t)s * 2 * L * Vs;
+        if (given_logits) {
+            memcpy(lg, given_logits + (size_t)s * 2 * L * Vs, sizeof(float) * (size_t)2 * L * Vs);
+        } else {
+            memset(lg, 0, sizeof(float) * (size_t)2 * L * Vs);
+            for (int b = 0; b < 2; ++b) {
+                win[0] = q->anchor[b];
+                for (int k = 1; k < Le; ++k) win[k] = q->tok[k];
+                int rc = oracle_forward(&c->md, &c->w, q->cache[b], win, Le, lg + (size_t)b * L * Vs);
+                if (rc) { free(win); return rc; }
+            }
+        }
+        for (int k = 0; k < Le; ++k)
+            oracle_sampling_row(lg + (size_t)k * Vs, lg + (size_t)(L + k) * Vs, Vs, c->sp.cfg_scale,
+                                c->sp.temperature, c->sp.top_k, c->new_e + (size_t)k * Vs, &c->new_Z[k]);
+        decide(c, s, Le, res);
+    }
+    free(win);
+    return OK;
+}
+
+int oracle_step(oracle_ctx *c, oracle_step_result *out) { return step_impl(c, NULL, out); }
+
+int oracle_step_from_logits(oracle_ctx *c, const float *logits, oracle_step_result *out) {
+    if (!logits) return EINVAL_;
+    return step_impl(c, logits, out);
+}
+
+int oracle_copy_logits(oracle_ctx *c, float *dst) {
+    if (!c || !dst) return EINVAL_;
+    memcpy(dst, c->logits, sizeof(float) * (size_t)c->n_seqs * 2 * c->L * c->Vs);
+    return OK;
+}
+
+int oracle_get_tokens(oracle_ctx *c, int32_t seq, int32_t *dst, int32_t cap, int32_t *n_out) {
+    if (!c || seq < 0 || seq >= c->n_seqs || !n_out) return EINVAL_;
+    const seq_state *q = &c->seq[seq];
+    int n = q->n_img < cap ? q->n_img : cap;
+    if (dst) memcpy(dst, q->out, sizeof(int32_t) * (size_t)n);
+    *n_out = q->n_img;
+    return OK;
+}
+
+int oracle_get_window(oracle_ctx *c, int32_t seq, int32_t *tokens, int32_t *ref_rows, int32_t *n_slots) {
+    if (!c || seq < 0 || seq >= c->n_seqs || !tokens || !ref_rows || !n_slots) return EINVAL_;
+    const seq_state *q = &c->seq[seq];
+    int remaining = q->n_image - q->n_img;
+    int Le = remaining < c->L ? remaining : c->L;
+    tokens[0] = q->anchor[0];
+    ref_rows[0] = -1;
+    for (int k = 1; k < c->L; ++k) { tokens[k] = k < Le ? q->tok[k] : 0; ref_rows[k] = k < Le ? q->ref_row[k] : -1; }
+    *n_slots = Le;
+    return OK;
+}
+
+/* Statistical helper for the end-to-end Theorem-1 pin: decodes one prompt
+ * n_trials times with seeds seed0, seed0 + 1, ... and histograms the decoded
+ * sequences, indexed sum_i (token_i - sample_lo) * V_s^i.  *n_steps receives
+ * the total number of oracle_step calls. */
+int oracle_decode_trials(const oracle_model_desc *md, const oracle_weights *w, const oracle_sampling *sp,
+                         const int32_t *cond, int32_t cond_len, const int32_t *uncond, int32_t uncond_len,
+                         int32_t n_image, uint64_t seed0, int64_t n_trials, int64_t *counts, int64_t *n_steps) {
+    int64_t steps = 0;
+    const int Vs = md->sample_hi - md->sample_lo;
+    for (int64_t t = 0; t < n_trials; ++t) {
+        oracle_sampling local = *sp;
+        local.seed = seed0 + (uint64_t)t;
+        oracle_ctx *c = NULL;
+        int rc = oracle_create(md, w, &local, 1, &c);
+        if (rc) return rc;
+        rc = oracle_prefill(c, 1, &cond, &cond_len, &uncond, &uncond_len, &n_image);
+        oracle_step_result res = {0, 0, 0, 0};
+        while (rc == 0 && !res.done) {
+            rc = oracle_step(c, &res);
+            steps += 1;
+        }
+        if (rc) { oracle_destroy(c); return rc; }
+        int64_t index = 0, mul = 1;
+        for (int i = 0; i < n_image; ++i) {
+            index += (int64_t)(c->seq[0].out[i] - md->sample_lo) * mul;
+            mul *= Vs;
+        }
+        counts[index] += 1;
+        oracle_destroy(c);
+    }
+    *n_steps = steps;
+    return OK;
+}
