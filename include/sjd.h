@@ -1,0 +1,204 @@
+/*
+ * sjd -- speculative Jacobi decoding (SJD++) of a discrete autoregressive
+ * image-token transformer on one AMD MI355X (gfx950).  C ABI.
+ *
+ * The library decodes image tokens after a text prompt with the iteration of
+ * Sec. 4.1 of the paper ("Speculative Jacobi Iteration"): a window of L tokens
+ * (the last final token followed by L-1 drafts) is run through ONE causal
+ * forward of the transformer against a paged KV cache, as a conditional /
+ * unconditional pair for classifier-free guidance (Sec. 5.1: guidance weight,
+ * top-K); drafts are accepted left to right with probability min(1, p/q)
+ * (Eq. 2), the first unaccepted position is redrawn from the residual
+ * normalise(max(0, p - q)) (Eq. 3), and each later draft is kept when its
+ * confidence p/q exceeds tau and redrawn from p otherwise (Eq. 4-5; tau = +inf
+ * is the rule without reuse, Eq. 6).
+ *
+ * Conventions
+ *  - every function returns SJD_OK (0) or a negative sjd_status and never
+ *    throws or aborts; sjd_last_error() gives a text for the last failure of a
+ *    context (or of sjd_create when passed NULL);
+ *  - "device" pointers are HIP device pointers on the current device, "host"
+ *    pointers are ordinary process memory;
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream);
+ *    it is borrowed and must outlive the context; all work of a context is
+ *    enqueued on it;
+ *  - a context is not thread-safe; different contexts are independent.
+ */
+#ifndef SJD_H
+#define SJD_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sjd_ctx sjd_ctx;
+
+enum sjd_status {
+    SJD_OK = 0,
+    SJD_EINVAL = -1,    /* bad argument or unsupported shape          */
+    SJD_ENOMEM = -2,    /* device or host allocation failed           */
+    SJD_ESTATE = -3,    /* call order violated                        */
+    SJD_EDEVICE = -4,   /* a HIP call failed                          */
+    SJD_ECAPACITY = -5  /* more sequences / context than created for  */
+};
+
+enum sjd_dtype { SJD_F32 = 0, SJD_BF16 = 1 };
+
+/* kernel_flags bits */
+enum {
+    SJD_KERNELS_REFERENCE = 1, /* use the plain (non-MFMA) GEMM and attention kernels */
+    SJD_NO_GRAPH = 2           /* never capture the step into a HIP graph             */
+};
+
+/* Architecture and capacities; plain data, copied by sjd_create.
+ * Pre-norm decoder blocks: RMSNorm, rotary embedding on q and k (rotate-half
+ * pairing (i, i + hd/2), angle pos * rope_theta^(-2i/hd)), grouped-query
+ * attention with scale 1/sqrt(hd), SwiGLU MLP, final RMSNorm, untied head.
+ * The paper fixes none of this (Sec. 3.1 only asks for a transformer that
+ * predicts a categorical distribution); it is the shape of the workloads. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ff;
+    int32_t vocab, sample_lo, sample_hi; /* token ids in [sample_lo, sample_hi) are sampled */
+    float rms_eps, rope_theta;
+    int32_t dtype;           /* sjd_dtype: storage of weights, activations fed to GEMMs, KV cache */
+    int32_t max_seqs;        /* prompts decoded together (each is a cond + uncond pair) */
+    int32_t max_ctx;         /* positions per branch: prompt + image tokens             */
+    int32_t window;          /* L >= 1: the last final token + L-1 drafts              */
+    int32_t kv_page_tokens;  /* tokens per KV page; multiple of 32; 0 = 64              */
+    int32_t kernel_flags;
+} sjd_model_desc;
+
+/* DEVICE pointers to weights of type `dtype`.  Linear weights are
+ * [out_features][in_features] row-major (y = W x); per-layer members are HOST
+ * arrays of n_layers device pointers.  sjd_create copies (and re-lays-out)
+ * everything it needs: nothing is referenced after it returns. */
+typedef struct {
+    const void *tok_emb;    /* [vocab][d_model] */
+    const void *final_norm; /* [d_model]        */
+    const void *lm_head;    /* [vocab][d_model] */
+    const void *const *attn_norm; /* [d_model]                     */
+    const void *const *wq;        /* [n_heads*hd][d_model]         */
+    const void *const *wk;        /* [n_kv_heads*hd][d_model]      */
+    const void *const *wv;        /* [n_kv_heads*hd][d_model]      */
+    const void *const *wo;        /* [d_model][n_heads*hd]         */
+    const void *const *mlp_norm;  /* [d_model]                     */
+    const void *const *w_gate;    /* [d_ff][d_model]               */
+    const void *const *w_up;      /* [d_ff][d_model]               */
+    const void *const *w_down;    /* [d_model][d_ff]               */
+} sjd_weights;
+
+/* Sampling distribution and decoding rule (Sec. 5.1).
+ * p = softmax over the top_k largest of z = (l_u + cfg_scale (l_c - l_u)) /
+ * temperature (ties at the k-th value kept).  Randomness is Philox4x32-10 keyed
+ * by `seed` with counter (step, row, sequence, 0). */
+typedef struct {
+    float cfg_scale, temperature;
+    int32_t top_k;
+    float reuse_tau;  /* 0.5 in the paper; +INF disables reuse (Eq. 6) */
+    uint64_t seed;
+    int32_t init_mode; /* 0 = new drafts drawn uniformly over the sampled ids (the only mode) */
+} sjd_sampling;
+
+typedef struct {
+    int32_t n_accepted;   /* drafts accepted this step (Eq. 2)                          */
+    int32_t n_finalized;  /* tokens made final this step = n_accepted + 1, 0 if done    */
+    int32_t reject_index; /* window slot of the first rejected draft, -1 if none        */
+    int32_t done;         /* 1 once all image tokens of the sequence are final          */
+} sjd_step_result;
+
+/* Creates a context on the current device: allocates KV pages for
+ * max_seqs * 2 * max_ctx positions, workspaces and decoding state; copies the
+ * weights.  Errors: SJD_EINVAL (null pointer, unsupported shape: bf16 needs
+ * hd % 32 == 0, d_model % 16 == 0, d_ff % 16 == 0), SJD_ENOMEM, SJD_EDEVICE. */
+int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd_sampling *sampling,
+               void *hip_stream, sjd_ctx **out);
+
+/* Starts n_seqs decodes (Sec. 4.1: "after prefilling the text tokens").  All
+ * arrays are HOST arrays of length n_seqs, read during the call only.  Every
+ * prompt token but the last is run through the model into the KV cache; the
+ * last one becomes the first window input; the L-1 drafts are drawn uniformly.
+ * May be called again to start new decodes.  Errors: SJD_EINVAL (null, length
+ * < 1, id outside the vocabulary), SJD_ECAPACITY (n_seqs > max_seqs or
+ * prompt + image tokens > max_ctx; nothing is enqueued), SJD_EDEVICE. */
+int sjd_prefill(sjd_ctx *ctx, int32_t n_seqs, const int32_t *const *cond_ids, const int32_t *cond_len,
+                const int32_t *const *uncond_ids, const int32_t *uncond_len, const int32_t *n_image_tokens);
+
+/* One speculative Jacobi iteration for every unfinished sequence (Sec. 4.1
+ * Steps 1-4).  out is a HOST array of n_seqs results.  The call returns after
+ * the step has completed on the device.  Sequences that are done are left
+ * untouched (n_finalized = 0, done = 1).  Errors: SJD_ESTATE (no prefill),
+ * SJD_EINVAL, SJD_EDEVICE. */
+int sjd_step(sjd_ctx *ctx, sjd_step_result *out);
+
+/* Frees everything the context owns.  NULL is allowed. */
+void sjd_destroy(sjd_ctx *ctx);
+
+/* Copies the image tokens of sequence `seq` that are final so far into dst
+ * (HOST, capacity cap, may be NULL when cap == 0); *n_out receives their count. */
+int sjd_get_tokens(sjd_ctx *ctx, int32_t seq, int32_t *dst, int32_t cap, int32_t *n_out);
+
+/* Current window of sequence `seq` (HOST arrays of length `window`): tokens
+ * (slot 0 = last final token) and per slot the output row of the previous step
+ * that is its reference distribution (-1 = uniform); *n_slots = slots in use. */
+int sjd_get_window(sjd_ctx *ctx, int32_t seq, int32_t *tokens, int32_t *ref_rows, int32_t *n_slots);
+
+const char *sjd_last_error(const sjd_ctx *ctx);
+
+/* fp32 logits of the last step, [n_seqs][2 (cond, uncond)][window][V_s],
+ * V_s = sample_hi - sample_lo, to HOST memory. */
+int sjd_debug_copy_logits(sjd_ctx *ctx, float *dst_host);
+
+/* Runs Steps 3-4 on caller-provided logits (HOST, layout as above) instead of
+ * the forward: the KV cache is not written, its length advances as usual. */
+int sjd_debug_step_from_logits(sjd_ctx *ctx, const float *logits_host, sjd_step_result *out);
+
+/* Per-kernel timing.  With tracing on, sjd_step brackets every kernel launch
+ * with HIP events on the context's stream and accumulates their durations.
+ * sjd_trace_read copies up to cap entries: name (static string), number of
+ * launches, total milliseconds; *n_out = number of kernel classes. */
+typedef struct {
+    const char *name;
+    int64_t launches;
+    double total_ms;
+} sjd_trace_entry;
+int sjd_trace_enable(sjd_ctx *ctx, int32_t on);
+int sjd_trace_reset(sjd_ctx *ctx);
+int sjd_trace_read(sjd_ctx *ctx, sjd_trace_entry *dst, int32_t cap, int32_t *n_out);
+
+/* ---- single operations, for kernel-level tests and microbenchmarks.
+ * All pointers are DEVICE pointers in plain row-major layouts; the calls
+ * allocate temporaries, run on `hip_stream` and return after completion. */
+
+/* C[M][N] (fp32) = A[M][K] * W[N][K]^T with the GEMM kernel the decoder uses
+ * for `dtype` (reference kernel if flags has SJD_KERNELS_REFERENCE).
+ * splits <= 0 lets the library choose the split-K factor.  `repeat` >= 1
+ * launches the kernel that many times; *avg_ms (HOST, may be NULL) receives the
+ * mean kernel time measured with HIP events. */
+int sjd_op_gemm(void *hip_stream, int32_t dtype, int32_t flags, const void *A, const void *W, float *C, int32_t M,
+                int32_t N, int32_t K, int32_t splits, int32_t repeat, float *avg_ms);
+
+/* Window attention of one (sequence, branch): q [n][H][hd], k and v
+ * [ctx + n][Hkv][hd] of `dtype` (the first ctx positions are the cache, the
+ * last n the window), out [n][H][hd] fp32.  Query i sees positions
+ * 0 .. ctx + i. */
+int sjd_op_window_attention(void *hip_stream, int32_t dtype, int32_t flags, const void *q, const void *k,
+                            const void *v, float *out, int32_t n, int32_t ctx, int32_t n_heads,
+                            int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens, int32_t repeat,
+                            float *avg_ms);
+
+/* Sampling distribution of `rows` positions: logits_c / logits_u [rows][V]
+ * fp32 -> e [rows][V] fp32 softmax weights (0 outside the top-k set) and
+ * Z [rows] uint64 integer normalisers. */
+int sjd_op_sampling_rows(void *hip_stream, const float *logits_c, const float *logits_u, float *e, uint64_t *Z,
+                         int32_t rows, int32_t V, float cfg_scale, float temperature, int32_t top_k,
+                         int32_t repeat, float *avg_ms);
+
+/* out[4*i .. 4*i+3] = Philox4x32-10(counter = (i, row, seq, 0), key = seed), i < n. */
+int sjd_op_philox(void *hip_stream, uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int32_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

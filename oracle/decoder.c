@@ -276,12 +276,30 @@ static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
     free(tok2);
 }
 
+/* Step 2 for sequence s: both branches over the current window; fills
+ * c->logits[s] (rows >= Le are zero).  Writes keys/values at the tentative
+ * positions cache->len .. cache->len + Le - 1 without committing them. */
+static int forward_current(oracle_ctx *c, int s, int Le) {
+    seq_state *q = &c->seq[s];
+    const int L = c->L, Vs = c->Vs;
+    float *lg = c->logits + (size_t)s * 2 * L * Vs;
+    int32_t *win = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
+    memset(lg, 0, sizeof(float) * (size_t)2 * L * Vs);
+    int rc = 0;
+    for (int b = 0; b < 2 && rc == 0; ++b) {
+        win[0] = q->anchor[b];
+        for (int k = 1; k < Le; ++k) win[k] = q->tok[k];
+        rc = oracle_forward(&c->md, &c->w, q->cache[b], win, Le, lg + (size_t)b * L * Vs);
+    }
+    free(win);
+    return rc;
+}
+
 static int step_impl(oracle_ctx *c, const float *given_logits, oracle_step_result *out) {
     if (!c || !out) return EINVAL_;
     if (!c->prefilled) return ESTATE_;
     const int L = c->L, Vs = c->Vs;
     c->step += 1;
-    int32_t *win = (int32_t *)malloc(sizeof(int32_t) * (size_t)L);
     for (int s = 0; s < c->n_seqs; ++s) {
         seq_state *q = &c->seq[s];
         oracle_step_result *res = &out[s];
@@ -295,20 +313,32 @@ static int step_impl(oracle_ctx *c, const float *given_logits, oracle_step_resul
         if (given_logits) {
             memcpy(lg, given_logits + (size_t)s * 2 * L * Vs, sizeof(float) * (size_t)2 * L * Vs);
         } else {
-            memset(lg, 0, sizeof(float) * (size_t)2 * L * Vs);
-            for (int b = 0; b < 2; ++b) {
-                win[0] = q->anchor[b];
-                for (int k = 1; k < Le; ++k) win[k] = q->tok[k];
-                int rc = oracle_forward(&c->md, &c->w, q->cache[b], win, Le, lg + (size_t)b * L * Vs);
-                if (rc) { free(win); return rc; }
-            }
+            int rc = forward_current(c, s, Le);
+            if (rc) return rc;
         }
         for (int k = 0; k < Le; ++k)
             oracle_sampling_row(lg + (size_t)k * Vs, lg + (size_t)(L + k) * Vs, Vs, c->sp.cfg_scale,
                                 c->sp.temperature, c->sp.top_k, c->new_e + (size_t)k * Vs, &c->new_Z[k]);
         decide(c, s, Le, res);
     }
-    free(win);
+    return OK;
+}
+
+/* The forward of the coming step only (no decision, no state change other
+ * than the tentative cache rows): logits [n_seqs][2][L][V_s]. */
+int oracle_peek_logits(oracle_ctx *c, float *dst) {
+    if (!c || !dst) return EINVAL_;
+    if (!c->prefilled) return ESTATE_;
+    const int L = c->L, Vs = c->Vs;
+    for (int s = 0; s < c->n_seqs; ++s) {
+        seq_state *q = &c->seq[s];
+        float *lg = c->logits + (size_t)s * 2 * L * Vs;
+        if (q->done) { memset(lg, 0, sizeof(float) * (size_t)2 * L * Vs); continue; }
+        const int remaining = q->n_image - q->n_img;
+        int rc = forward_current(c, s, remaining < L ? remaining : L);
+        if (rc) return rc;
+    }
+    memcpy(dst, c->logits, sizeof(float) * (size_t)c->n_seqs * 2 * L * Vs);
     return OK;
 }
 

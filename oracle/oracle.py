@@ -73,6 +73,7 @@ def lib():
         L.oracle_step.argtypes = [C.c_void_p, C.POINTER(StepResult)]
         L.oracle_step_from_logits.argtypes = [C.c_void_p, _FP, C.POINTER(StepResult)]
         L.oracle_copy_logits.argtypes = [C.c_void_p, _FP]
+        L.oracle_peek_logits.argtypes = [C.c_void_p, _FP]
         L.oracle_get_tokens.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                                         C.POINTER(C.c_int32)]
         L.oracle_get_window.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
@@ -300,6 +301,14 @@ class Oracle:
     def logits(self):
         out = np.zeros((self.n_seqs, 2, self.L, self.Vs), dtype=np.float32)
         lib().oracle_copy_logits(self.ctx, _fp(out))
+        return out
+
+    def peek_logits(self):
+        """The oracle's own forward for the current window, without deciding anything."""
+        out = np.zeros((self.n_seqs, 2, self.L, self.Vs), dtype=np.float32)
+        rc = lib().oracle_peek_logits(self.ctx, _fp(out))
+        if rc != 0:
+            raise RuntimeError(f"oracle_peek_logits failed: {rc}")
         return out
 
     def tokens(self, seq=0):

@@ -104,6 +104,10 @@ int oracle_step(oracle_ctx *, oracle_step_result *out /* [n_seqs] */);
  * logits is [n_seqs][2 (cond, uncond)][L][V_s] fp32; the KV cache is not
  * touched (its length still advances). */
 int oracle_step_from_logits(oracle_ctx *, const float *logits, oracle_step_result *out);
+/* Forward of the coming step only: logits of the current window, no decision
+ * and no state change; a following oracle_step_from_logits may then advance
+ * the decode on other logits for the same window. */
+int oracle_peek_logits(oracle_ctx *, float *dst);
 /* Logits of the most recent oracle_step, [n_seqs][2][L][V_s]. */
 int oracle_copy_logits(oracle_ctx *, float *dst);
 int oracle_get_tokens(oracle_ctx *, int32_t seq, int32_t *dst, int32_t cap, int32_t *n_out);

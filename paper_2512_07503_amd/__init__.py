@@ -1,0 +1,6 @@
+"""SJD++ (speculative Jacobi decoding with token reuse) on one MI355X: thin Python binding of libsjd.so.
+
+Only argument marshalling lives here; every step of the decoding path runs in the HIP library.
+"""
+from .binding import (SjdError, Decoder, lib, library_path, op_gemm, op_window_attention, op_sampling_rows,  # noqa: F401
+                      op_philox, KERNELS_REFERENCE, NO_GRAPH, F32, BF16)

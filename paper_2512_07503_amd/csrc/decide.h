@@ -1,0 +1,63 @@
+// Host-side launch interface of the decision stage (sampling distribution, verification,
+// residual / refresh draws, window update).  Implemented in decide.hip, which is compiled with
+// floating-point contraction off: its results are specified bit for bit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sjd.h"
+
+// Device-resident decoding state of a context (all pointers are device pointers).
+struct DecideState {
+    int32_t L;         // window
+    int32_t V;         // sampled vocabulary size V_s
+    int32_t lo;        // sample_lo
+    int32_t max_img;   // capacity of out_tok per sequence
+    int32_t *win_tok;  // [S][L]   window tokens (slot 0 unused)
+    int32_t *anchor;   // [S][2]   first window input of the cond / uncond branch
+    int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform
+    int32_t *n_img;    // [S]      image tokens final so far
+    int32_t *n_image;  // [S]      image tokens wanted
+    int32_t *kv_len;   // [S][2]   committed cache positions per branch
+    int32_t *Le;       // [S]      effective window of the coming / current step, 0 = done or unused
+    int32_t *out_tok;  // [S][max_img]
+    int32_t *acc_len;  // [S]      accepted drafts of the current step
+    int32_t *cand;     // [S][L]   per output row: the token drawn (or kept) there this step
+    uint32_t *step;    // [1]      step counter (0 after prefill)
+    float *e_buf[2];   // [S][L][V] softmax weights, ping-pong by step parity
+    uint64_t *Z_buf[2];// [S][L]
+    sjd_step_result *res; // [S]
+};
+
+struct SamplingParams {
+    float cfg_scale, inv_temperature, tau;
+    int32_t top_k;
+    uint64_t seed;
+};
+
+// Rows of the forward: token and position per GEMM row, cache length and active rows per segment
+// (segment = sequence * 2 + branch).
+struct RowMap {
+    int32_t *row_tok;  // [S*2*L]  token id, -1 = inactive row
+    int32_t *row_pos;  // [S*2*L]
+    int32_t *seg_kv;   // [S*2]
+    int32_t *seg_n;    // [S*2]
+};
+
+hipError_t launch_init_window(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs, int max_seqs,
+                              const int32_t *prompt_last /*[S][2]*/, const int32_t *prompt_len /*[S][2]*/,
+                              const int32_t *n_image /*[S]*/);
+hipError_t launch_stage_window(hipStream_t st, const DecideState &d, const RowMap &rm, int n_seqs);
+hipError_t launch_stage_prompt(hipStream_t st, const RowMap &rm, const int32_t *prompt /*[S][2][max_prompt]*/,
+                               const int32_t *prompt_len, int max_prompt, int chunk, int L, int n_seqs);
+// logits: [n_seqs][2][L][V]
+hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, const float *logits,
+                              int n_seqs);
+hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
+hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
+hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
+
+// stand-alone forms for kernel tests
+hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,
+                                      int V, const SamplingParams &sp);
+hipError_t launch_philox_fill(hipStream_t st, uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n);

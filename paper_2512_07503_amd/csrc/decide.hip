@@ -1,0 +1,541 @@
+// Decision stage of one speculative Jacobi iteration (Sec. 4.1 of the paper, Steps 3 and 4) and the
+// sampling distribution it works on (Sec. 3.1 top-K sampling, Sec. 5.1 guidance weight and threshold).
+//
+// Every result of this file is specified bit for bit as a function of the fp32 logits:
+//   z      = fma(cfg_scale, l_c - l_u, l_u) * (1 / temperature)              in fp32
+//   kept   = { v : z_v >= K-th largest z }   (ties kept)
+//   e_v    = EXP(z_v - max z) for kept v, else 0; EXP is the fixed fp32 operation sequence below
+//   w_v    = trunc(e_v * 2^40) as uint64,  Z = sum_v w_v                      probability = w / Z
+//   accept (Eq. 2)   r * Q < P          with r = (u32 + 1/2) 2^-32, P = (double)w_p / (double)Z_p
+//   keep   (Eq. 4-5) P > (double)tau * Q
+//   draw   from p    first v with prefix_w(v) > floor(u64 * Z / 2^64)
+//   draw   (Eq. 3)   same over rho_v = trunc(max(0, P_v - Q_v) * 2^44); if all rho are 0, from p
+// Uniform numbers are Philox4x32-10 (Salmon et al., SC'11) with key = seed and counter
+// (step, row, sequence, 0): word 0 = acceptance test of the draft verified at `row`, words 1-2 = the
+// 64-bit uniform of the one draw made at `row`, word 3 = a fresh uniform draft.
+//
+// This translation unit must be compiled with -ffp-contract=off.
+#include "decide.h"
+
+#include "common.hip.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+// ------------------------------------------------------------------------------------ primitives
+SJD_D void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+SJD_D void draw_words(uint64_t seed, uint32_t step, uint32_t row, uint32_t seq, uint32_t out[4]) {
+    philox4x32_10(step, row, seq, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), out);
+}
+
+// EXP(x), x <= 0: k = rint(x log2 e), r = x - k ln2 (two-constant split), degree-6 Taylor polynomial
+// by Horner with fused multiply-adds, times 2^k built in the exponent field; 0 below -60.
+SJD_D float exp_neg(float x) {
+    if (x < -60.0f) return 0.0f;
+    float kf = __builtin_rintf(x * 0x1.715476p+0f);
+    float r = __builtin_fmaf(kf, -0x1.62ep-1f, x);
+    r = __builtin_fmaf(kf, -0x1.0bfbe8p-15f, r);
+    float p = 0x1.6c16c2p-10f;
+    p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    int k = (int)kf;
+    float scale = __builtin_bit_cast(float, (uint32_t)(k + 127) << 23);
+    return p * scale;
+}
+
+SJD_D uint64_t weight_of(float e) { return (uint64_t)(e * 0x1p40f); }
+
+SJD_D double prob(uint64_t w, uint64_t Z) { return (double)w / (double)Z; }
+
+SJD_D bool accept_rule(uint32_t u32, uint64_t wp, uint64_t Zp, uint64_t wq, uint64_t Zq) {
+    double r = ((double)u32 + 0.5) * 0x1p-32;
+    double P = prob(wp, Zp), Q = prob(wq, Zq);
+    return r * Q < P;
+}
+
+SJD_D bool keep_rule(float tau, uint64_t wp, uint64_t Zp, uint64_t wq, uint64_t Zq) {
+    double P = prob(wp, Zp), Q = prob(wq, Zq);
+    return P > (double)tau * Q;
+}
+
+SJD_D uint64_t mulhi64(uint64_t a, uint64_t b) { return __umul64hi(a, b); }
+
+SJD_D uint64_t residual_weight(double P, double Q) {
+    double d = P - Q;
+    return d > 0.0 ? (uint64_t)(d * 0x1p44) : 0ull;
+}
+
+// float -> unsigned key with the same order (-0 is folded into +0)
+SJD_D uint32_t order_key(float z) {
+    uint32_t b = __builtin_bit_cast(uint32_t, z);
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+SJD_D float key_to_float(uint32_t k) {
+    uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    return __builtin_bit_cast(float, b);
+}
+
+SJD_D float guided(float lc, float lu, float s, float inv_t) {
+    float d = lc - lu;
+    return __builtin_fmaf(s, d, lu) * inv_t;
+}
+
+// --------------------------------------------------------------------------- block-wide helpers
+SJD_D uint64_t shfl_down_u64(uint64_t v, int delta) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_down(lo, delta, 64);
+    hi = __shfl_down(hi, delta, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// sum of one uint64 per thread over the block (integer: order does not matter); result in all threads
+SJD_D uint64_t block_sum_u64(uint64_t v, uint64_t *scratch /* >= 17 entries */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    for (int d = 32; d > 0; d >>= 1) v += shfl_down_u64(v, d);
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t t = 0;
+        for (int i = 0; i < nw; ++i) t += scratch[i];
+        scratch[16] = t;
+    }
+    __syncthreads();
+    return scratch[16];
+}
+
+SJD_D uint32_t block_max_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    for (int d = 32; d > 0; d >>= 1) {
+        uint32_t o = __shfl_down(v, d, 64);
+        v = o > v ? o : v;
+    }
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < nw; ++i) t = scratch[i] > t ? scratch[i] : t;
+        scratch[16] = t;
+    }
+    __syncthreads();
+    return scratch[16];
+}
+
+// ------------------------------------------------------------------ a10: the sampling distribution
+// One block per row.  Radix select (4 passes of 8 bits over order keys) finds the K-th largest guided
+// logit exactly; the logits are re-read from L2 in every pass.
+struct SampleRowsArgs {
+    const float *lc_base, *lu_base;  // row r = (s, k): base + s * seq_stride + k * V
+    long seq_stride;
+    int L;                           // rows per sequence
+    float *e_base[2];                // + (s * L + k) * V; index = *step & 1 (0 when step == NULL)
+    uint64_t *Z_base[2];             // + s * L + k
+    const uint32_t *step;
+    const int32_t *Le;               // [S] active rows per sequence, NULL = all
+    int V, top_k;
+    float cfg_scale, inv_t;
+};
+
+__global__ void sample_rows_kernel(SampleRowsArgs a) {
+    const int r = blockIdx.x, s = r / a.L, k = r % a.L;
+    if (a.Le && k >= a.Le[s]) return;
+    const float *lc = a.lc_base + (long)s * a.seq_stride + (long)k * a.V;
+    const float *lu = a.lu_base + (long)s * a.seq_stride + (long)k * a.V;
+    const uint32_t par = a.step ? (*a.step & 1u) : 0u;
+    float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
+    const int V = a.V, tid = threadIdx.x, nt = blockDim.x;
+
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sel[2];
+    __shared__ uint32_t scratch32[17];
+    __shared__ uint64_t scratch64[17];
+
+    uint32_t kmax = 0;
+    for (int v = tid; v < V; v += nt) {
+        uint32_t key = order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t));
+        kmax = key > kmax ? key : kmax;
+    }
+    kmax = block_max_u32(kmax, scratch32);
+    const float m = key_to_float(kmax);
+
+    uint32_t thresh = 0;  // keep everything
+    if (a.top_k < V) {
+        uint32_t prefix = 0, mask = 0, want = (uint32_t)a.top_k;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            for (int i = tid; i < 256; i += nt) hist[i] = 0;
+            __syncthreads();
+            for (int v = tid; v < V; v += nt) {
+                uint32_t key = order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t));
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t cum = 0;
+                int b = 255;
+                for (; b > 0; --b) {
+                    if (cum + hist[b] >= want) break;
+                    cum += hist[b];
+                }
+                sel[0] = (uint32_t)b;
+                sel[1] = want - cum;  // rank wanted inside the selected bin
+            }
+            __syncthreads();
+            prefix |= sel[0] << shift;
+            mask |= 255u << shift;
+            want = sel[1];
+            __syncthreads();
+        }
+        thresh = prefix;
+    }
+
+    uint64_t zsum = 0;
+    for (int v = tid; v < V; v += nt) {
+        float z = guided(lc[v], lu[v], a.cfg_scale, a.inv_t);
+        float ev = order_key(z) >= thresh ? exp_neg(z - m) : 0.0f;
+        e[v] = ev;
+        zsum += weight_of(ev);
+    }
+    zsum = block_sum_u64(zsum, scratch64);
+    if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
+}
+
+// --------------------------------------------------------------------------------- window set-up
+__global__ void init_window_kernel(DecideState d, uint64_t seed, int n_seqs, const int32_t *prompt_last,
+                                   const int32_t *prompt_len, const int32_t *n_image) {
+    const int s = blockIdx.x;
+    if (s == 0 && threadIdx.x == 0) *d.step = 0u;
+    if (s >= n_seqs) {
+        if (threadIdx.x == 0) { d.Le[s] = 0; d.n_img[s] = 0; d.n_image[s] = 0; }
+        return;
+    }
+    const int N = n_image[s];
+    const int Le = N < d.L ? N : d.L;
+    if (threadIdx.x == 0) {
+        d.n_img[s] = 0;
+        d.n_image[s] = N;
+        d.Le[s] = Le;
+        for (int b = 0; b < 2; ++b) {
+            d.kv_len[s * 2 + b] = prompt_len[s * 2 + b] - 1;
+            d.anchor[s * 2 + b] = prompt_last[s * 2 + b];
+        }
+    }
+    for (int k = threadIdx.x; k < d.L; k += blockDim.x) {
+        int tok = 0;
+        if (k >= 1 && k < Le) {
+            uint32_t w[4];
+            draw_words(seed, 0u, (uint32_t)k, (uint32_t)s, w);
+            tok = d.lo + (int)__umulhi(w[3], (uint32_t)d.V);
+        }
+        d.win_tok[s * d.L + k] = tok;
+        d.ref_row[s * d.L + k] = -1;
+    }
+}
+
+// Rows of the coming forward over the window; also advances the step counter.
+__global__ void stage_window_kernel(DecideState d, RowMap rm, int n_seqs) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m == 0) *d.step += 1u;
+    if (m >= n_seqs * 2 * d.L) return;
+    const int k = m % d.L, seg = m / d.L, s = seg >> 1;
+    const int Le = d.Le[s];
+    const int kv = d.kv_len[seg];
+    rm.row_tok[m] = k < Le ? (k == 0 ? d.anchor[seg] : d.win_tok[s * d.L + k]) : -1;
+    rm.row_pos[m] = kv + k;
+    if (k == 0) { rm.seg_kv[seg] = kv; rm.seg_n[seg] = Le; }
+}
+
+// Rows of prefill chunk `chunk`: prompt positions chunk*L .. chunk*L + L - 1 of every segment, as far
+// as they lie before the last prompt token.
+__global__ void stage_prompt_kernel(RowMap rm, const int32_t *prompt, const int32_t *prompt_len, int max_prompt, int chunk,
+                                    int L, int n_seqs) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= n_seqs * 2 * L) return;
+    const int k = m % L, seg = m / L;
+    const int start = chunk * L;
+    int n = prompt_len[seg] - 1 - start;
+    n = n < 0 ? 0 : (n > L ? L : n);
+    rm.row_tok[m] = k < n ? prompt[(long)seg * max_prompt + start + k] : -1;
+    rm.row_pos[m] = start + k;
+    if (k == 0) { rm.seg_kv[seg] = start; rm.seg_n[seg] = n; }
+}
+
+// ------------------------------------------------------------------- a11: verification (Eq. 2)
+// One block per sequence; every draft is tested in parallel, the first rejection is found with a
+// wavefront ballot per 64 drafts and a minimum across wavefronts.
+__global__ void verify_kernel(DecideState d, uint64_t seed) {
+    const int s = blockIdx.x, L = d.L, V = d.V;
+    const int Le = d.Le[s];
+    if (Le == 0) return;
+    const uint32_t step = *d.step;
+    const float *e_new = d.e_buf[step & 1u] + (long)s * L * V;
+    const float *e_ref = d.e_buf[(step & 1u) ^ 1u] + (long)s * L * V;
+    const uint64_t *Z_new = d.Z_buf[step & 1u] + s * L;
+    const uint64_t *Z_ref = d.Z_buf[(step & 1u) ^ 1u] + s * L;
+    __shared__ int first_reject;
+    if (threadIdx.x == 0) first_reject = Le;
+    __syncthreads();
+    for (int base = 1; base < Le; base += blockDim.x) {
+        const int k = base + threadIdx.x;
+        bool rejected = false;
+        if (k < Le) {
+            uint32_t w[4];
+            draw_words(seed, step, (uint32_t)(k - 1), (uint32_t)s, w);
+            const int x = d.win_tok[s * L + k] - d.lo;
+            const uint64_t wp = weight_of(e_new[(long)(k - 1) * V + x]);
+            const int rr = d.ref_row[s * L + k];
+            const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
+            const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+            rejected = !accept_rule(w[0], wp, Z_new[k - 1], wq, Zq);
+        }
+        const uint64_t mask = __ballot(rejected);
+        if ((threadIdx.x & 63) == 0 && mask != 0ull) atomicMin(&first_reject, base + (threadIdx.x & ~63) + __builtin_ctzll(mask));
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) d.acc_len[s] = first_reject - 1;
+}
+
+// ---------------------------------------------------- a12 / a13: the draws of a step (Eq. 3, Eq. 5)
+// Block-wide inverse CDF over integer weights weight(v), v in [0, V): returns the first v whose
+// inclusive prefix sum exceeds floor(u64 * total / 2^64), or -1 when total == 0.
+template <typename F>
+SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [blockDim.x + 2] shared */) {
+    const int nt = blockDim.x, tid = threadIdx.x;
+    const int chunk = (V + nt - 1) / nt;
+    const int v0 = tid * chunk, v1 = v0 + chunk < V ? v0 + chunk : V;
+    uint64_t local = 0;
+    for (int v = v0; v < v1; ++v) local += weight(v);
+    __syncthreads();
+    sums[tid] = local;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t run = 0;
+        for (int i = 0; i < nt; ++i) { uint64_t t = sums[i]; sums[i] = run; run += t; }
+        sums[nt] = run;
+        sums[nt + 1] = (uint64_t)(int64_t)-1;
+    }
+    __syncthreads();
+    const uint64_t total = sums[nt];
+    if (total == 0) return -1;
+    const uint64_t target = mulhi64(u64, total);
+    const uint64_t excl = sums[tid];
+    if (excl <= target && target < excl + local) {
+        uint64_t prefix = excl;
+        for (int v = v0; v < v1; ++v) {
+            prefix += weight(v);
+            if (prefix > target) { sums[nt + 1] = (uint64_t)v; break; }
+        }
+    }
+    __syncthreads();
+    return (int)(int64_t)sums[nt + 1];
+}
+
+// One block per output row k of every sequence.  With a accepted drafts:
+//   k == a            the token that becomes final: residual draw (Eq. 3) against the reference of the
+//                     rejected draft, or a plain draw from row a when every draft was accepted;
+//   a < k <= Le - 2   slot k + 1: kept if p > tau q (Eq. 4-5) else redrawn from row k;
+//   k == Le - 1 > a   no draft was predicted by this row: its slot is drawn from it.
+__global__ void draw_kernel(DecideState d, uint64_t seed, float tau) {
+    const int r = blockIdx.x, L = d.L, V = d.V, s = r / L, k = r % L;
+    const int Le = d.Le[s];
+    if (k >= Le) return;
+    const int a = d.acc_len[s];
+    if (k < a) return;
+    const uint32_t step = *d.step;
+    const float *e_new = d.e_buf[step & 1u] + (long)s * L * V;
+    const float *e_ref = d.e_buf[(step & 1u) ^ 1u] + (long)s * L * V;
+    const uint64_t *Z_new = d.Z_buf[step & 1u] + s * L;
+    const uint64_t *Z_ref = d.Z_buf[(step & 1u) ^ 1u] + s * L;
+    extern __shared__ uint64_t sums[];
+
+    uint32_t w[4];
+    draw_words(seed, step, (uint32_t)k, (uint32_t)s, w);
+    const uint64_t u64 = ((uint64_t)w[1] << 32) | w[2];
+    const float *pk = e_new + (long)k * V;
+    const uint64_t Zp = Z_new[k];
+    auto from_p = [&](int v) { return weight_of(pk[v]); };
+
+    int tok;
+    if (k == a && a < Le - 1) {
+        const int rr = d.ref_row[s * L + a + 1];
+        const float *qrow = rr < 0 ? nullptr : e_ref + (long)rr * V;
+        const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+        auto resid = [&](int v) {
+            double P = prob(weight_of(pk[v]), Zp);
+            double Q = prob(qrow ? weight_of(qrow[v]) : 1ull, Zq);
+            return residual_weight(P, Q);
+        };
+        tok = block_inverse_cdf(resid, V, u64, sums);
+        if (tok < 0) tok = block_inverse_cdf(from_p, V, u64, sums);
+    } else if (k > a && k <= Le - 2) {
+        const int x = d.win_tok[s * L + k + 1] - d.lo;
+        const int rr = d.ref_row[s * L + k + 1];
+        const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
+        const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+        if (keep_rule(tau, weight_of(pk[x]), Zp, wq, Zq)) {
+            tok = x;
+        } else {
+            tok = block_inverse_cdf(from_p, V, u64, sums);
+        }
+    } else {
+        tok = block_inverse_cdf(from_p, V, u64, sums);
+    }
+    if (threadIdx.x == 0) d.cand[s * L + k] = d.lo + tok;
+}
+
+// ----------------------------------------------- a14: finalise, shift the window, refill, commit
+__global__ void commit_kernel(DecideState d, uint64_t seed) {
+    const int s = blockIdx.x, L = d.L;
+    const int Le = d.Le[s];
+    sjd_step_result *res = d.res + s;
+    if (Le == 0) {
+        if (threadIdx.x == 0) { res->n_accepted = 0; res->n_finalized = 0; res->reject_index = -1; res->done = 1; }
+        return;
+    }
+    const uint32_t step = *d.step;
+    const int a = d.acc_len[s];
+    const int n_img = d.n_img[s], N = d.n_image[s];
+    const int y = d.cand[s * L + a];
+    int32_t *out = d.out_tok + (long)s * d.max_img;
+    for (int k = 1 + threadIdx.x; k <= a; k += blockDim.x) out[n_img + k - 1] = d.win_tok[s * L + k];
+    const int remaining = N - (n_img + a + 1);
+    const int Le2 = remaining < L ? remaining : L;
+    __syncthreads();  // every read of the old window is done
+    for (int k2 = 1 + threadIdx.x; k2 < L; k2 += blockDim.x) {
+        int tok = 0, ref = -1;
+        if (k2 < Le2) {
+            const int k = k2 + a + 1;
+            if (k <= Le) {           // slot k of this step (k == Le: the slot predicted by the last row)
+                tok = d.cand[s * L + k - 1];
+                ref = k - 1;
+            } else {                 // a slot that never had a row: fresh uniform draft
+                uint32_t w[4];
+                draw_words(seed, step, (uint32_t)k, (uint32_t)s, w);
+                tok = d.lo + (int)__umulhi(w[3], (uint32_t)d.V);
+            }
+        }
+        d.win_tok[s * L + k2] = tok;
+        d.ref_row[s * L + k2] = ref;
+    }
+    if (threadIdx.x == 0) {
+        out[n_img + a] = y;
+        d.n_img[s] = n_img + a + 1;
+        d.kv_len[s * 2] += a + 1;
+        d.kv_len[s * 2 + 1] += a + 1;
+        d.anchor[s * 2] = y;
+        d.anchor[s * 2 + 1] = y;
+        d.Le[s] = Le2;  // 0 when the image is complete
+        res->n_accepted = a;
+        res->n_finalized = a + 1;
+        res->reject_index = a < Le - 1 ? a + 1 : -1;
+        res->done = remaining == 0 ? 1 : 0;
+    }
+}
+
+__global__ void philox_fill_kernel(uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t w[4];
+    draw_words(seed, (uint32_t)i, row, seq, w);
+    for (int j = 0; j < 4; ++j) out[4 * i + j] = w[j];
+}
+
+int rows_block(int V) { return V >= 16384 ? 1024 : 256; }
+
+}  // namespace
+
+hipError_t launch_init_window(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs, int max_seqs,
+                              const int32_t *prompt_last, const int32_t *prompt_len, const int32_t *n_image) {
+    init_window_kernel<<<max_seqs, 64, 0, st>>>(d, sp.seed, n_seqs, prompt_last, prompt_len, n_image);
+    return hipGetLastError();
+}
+
+hipError_t launch_stage_window(hipStream_t st, const DecideState &d, const RowMap &rm, int n_seqs) {
+    const int M = n_seqs * 2 * d.L;
+    stage_window_kernel<<<ceil_div(M, 256), 256, 0, st>>>(d, rm, n_seqs);
+    return hipGetLastError();
+}
+
+hipError_t launch_stage_prompt(hipStream_t st, const RowMap &rm, const int32_t *prompt, const int32_t *prompt_len,
+                               int max_prompt, int chunk, int L, int n_seqs) {
+    const int M = n_seqs * 2 * L;
+    stage_prompt_kernel<<<ceil_div(M, 256), 256, 0, st>>>(rm, prompt, prompt_len, max_prompt, chunk, L, n_seqs);
+    return hipGetLastError();
+}
+
+hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, const float *logits,
+                              int n_seqs) {
+    SampleRowsArgs a;
+    a.lc_base = logits;
+    a.lu_base = logits + (long)d.L * d.V;
+    a.seq_stride = 2l * d.L * d.V;
+    a.L = d.L;
+    a.e_base[0] = d.e_buf[0]; a.e_base[1] = d.e_buf[1];
+    a.Z_base[0] = d.Z_buf[0]; a.Z_base[1] = d.Z_buf[1];
+    a.step = d.step;
+    a.Le = d.Le;
+    a.V = d.V;
+    a.top_k = sp.top_k;
+    a.cfg_scale = sp.cfg_scale;
+    a.inv_t = sp.inv_temperature;
+    sample_rows_kernel<<<n_seqs * d.L, rows_block(d.V), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,
+                                      int V, const SamplingParams &sp) {
+    SampleRowsArgs a;
+    a.lc_base = lc;
+    a.lu_base = lu;
+    a.seq_stride = 0;
+    a.L = rows;
+    a.e_base[0] = a.e_base[1] = e;
+    a.Z_base[0] = a.Z_base[1] = Z;
+    a.step = nullptr;
+    a.Le = nullptr;
+    a.V = V;
+    a.top_k = sp.top_k;
+    a.cfg_scale = sp.cfg_scale;
+    a.inv_t = sp.inv_temperature;
+    sample_rows_kernel<<<rows, rows_block(V), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
+    verify_kernel<<<n_seqs, 256, 0, st>>>(d, sp.seed);
+    return hipGetLastError();
+}
+
+hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
+    const int nt = 256;
+    draw_kernel<<<n_seqs * d.L, nt, (nt + 2) * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau);
+    return hipGetLastError();
+}
+
+hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
+    commit_kernel<<<n_seqs, 64, 0, st>>>(d, sp.seed);
+    return hipGetLastError();
+}
+
+hipError_t launch_philox_fill(hipStream_t st, uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n) {
+    philox_fill_kernel<<<ceil_div(n, 256), 256, 0, st>>>(seed, row, seq, out, n);
+    return hipGetLastError();
+}

@@ -1,0 +1,652 @@
+// Host side of the sjd library: the C ABI of include/sjd.h, the context, the paged KV cache and the
+// fixed kernel sequence of one speculative Jacobi iteration (Sec. 4.1 of the paper, Steps 1-4).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "common.hip.h"
+#include "decide.h"
+#include "kernels_attention.hip.h"
+#include "kernels_forward.hip.h"
+#include "kernels_gemm.hip.h"
+
+void sjd_set_error(char *buf, const char *fmt, ...) {
+    if (!buf) return;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, 512, fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+char g_create_error[512] = "";
+
+enum KernelClass {
+    KC_STAGE = 0, KC_EMBED, KC_ADDNORM, KC_GEMM_QKV, KC_ROPE_KV, KC_ATTENTION, KC_GEMM_O, KC_GEMM_GATEUP, KC_SWIGLU,
+    KC_GEMM_DOWN, KC_GEMM_HEAD, KC_SAMPLE_ROWS, KC_VERIFY, KC_DRAW, KC_COMMIT, KC_COUNT
+};
+const char *const kKernelClassName[KC_COUNT] = {
+    "stage_rows", "embed", "addnorm", "gemm_qkv", "rope_kv_write", "window_attention", "gemm_out", "gemm_gate_up", "swiglu",
+    "gemm_down", "gemm_head", "sample_rows", "verify", "draw", "commit"};
+
+struct Tracer {
+    bool on = false;
+    std::vector<hipEvent_t> pool;   // pairs: start, stop
+    std::vector<int> cls;           // class of each recorded pair
+    size_t used = 0;
+    int64_t launches[KC_COUNT] = {0};
+    double total_ms[KC_COUNT] = {0};
+};
+
+struct LayerWeights {
+    float *attn_norm = nullptr, *mlp_norm = nullptr;
+    void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdown = nullptr;
+};
+
+}  // namespace
+
+struct sjd_ctx {
+    sjd_model_desc md;
+    sjd_sampling sampling;
+    SamplingParams sp;
+    hipStream_t stream = nullptr;
+    char err[512] = "";
+    int hd = 0, Vs = 0, L = 0, S = 0, n_seqs = 0, pt = 0, pps = 0, n_pages = 0, max_visible = 0;
+    size_t esize = 0;
+    bool prefilled = false, all_done = false;
+    // weights (owned)
+    void *tok_emb = nullptr, *lm_head = nullptr;
+    float *final_norm = nullptr;
+    std::vector<LayerWeights> layers;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+    // KV pages
+    void *kpool = nullptr, *vpool = nullptr;
+    size_t pool_layer_bytes = 0;
+    int32_t *page_table = nullptr;
+    // workspaces
+    float *x = nullptr, *partial = nullptr, *logits = nullptr;
+    void *xn = nullptr, *q = nullptr, *attn = nullptr, *h = nullptr;
+    size_t partial_elems = 0;
+    RowMap rm{};
+    DecideState ds{};
+    int32_t *prompt_dev = nullptr, *prompt_len_dev = nullptr, *prompt_last_dev = nullptr, *n_image_dev = nullptr;
+    sjd_step_result *res_host = nullptr;
+    std::vector<void *> allocations;
+    Tracer tracer;
+};
+
+namespace {
+
+template <typename P> int dev_alloc(sjd_ctx *c, P **out, size_t bytes, bool zero = true) {
+    void *p = nullptr;
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        sjd_set_error(c->err, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        return SJD_ENOMEM;
+    }
+    c->allocations.push_back(p);
+    if (zero) {
+        e = hipMemsetAsync(p, 0, bytes, c->stream);
+        if (e != hipSuccess) {
+            sjd_set_error(c->err, "hipMemsetAsync failed: %s", hipGetErrorString(e));
+            return SJD_EDEVICE;
+        }
+    }
+    *out = reinterpret_cast<P *>(p);
+    return SJD_OK;
+}
+
+void trace_begin(sjd_ctx *c, int cls) {
+    Tracer &t = c->tracer;
+    if (!t.on) return;
+    if (t.used + 2 > t.pool.size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { t.on = false; return; }
+        t.pool.push_back(a);
+        t.pool.push_back(b);
+    }
+    t.cls.push_back(cls);
+    (void)hipEventRecord(t.pool[t.used], c->stream);
+}
+void trace_end(sjd_ctx *c) {
+    Tracer &t = c->tracer;
+    if (!t.on) return;
+    (void)hipEventRecord(t.pool[t.used + 1], c->stream);
+    t.used += 2;
+}
+// after the stream has been synchronised
+void trace_collect(sjd_ctx *c) {
+    Tracer &t = c->tracer;
+    for (size_t i = 0; i + 1 < t.used; i += 2) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, t.pool[i], t.pool[i + 1]) == hipSuccess) {
+            t.total_ms[t.cls[i / 2]] += ms;
+            t.launches[t.cls[i / 2]] += 1;
+        }
+    }
+    t.used = 0;
+    t.cls.clear();
+}
+
+#define SJD_LAUNCH(c, cls, expr)                                                                   \
+    do {                                                                                           \
+        trace_begin(c, cls);                                                                       \
+        hipError_t e__ = (expr);                                                                   \
+        trace_end(c);                                                                              \
+        if (e__ != hipSuccess) {                                                                   \
+            sjd_set_error((c)->err, "launch of %s failed: %s", kKernelClassName[cls], hipGetErrorString(e__)); \
+            return SJD_EDEVICE;                                                                    \
+        }                                                                                          \
+    } while (0)
+
+template <typename F> hipError_t after(F &&f) {
+    f();
+    return hipGetLastError();
+}
+
+bool use_reference(const sjd_ctx *c) { return c->md.dtype == SJD_F32 || (c->md.kernel_flags & SJD_KERNELS_REFERENCE); }
+
+// ------------------------------------------------------------------------------------- GEMM dispatch
+// C_partial[splits][M][N]; returns the number of splits written.
+template <typename T>
+int run_gemm(sjd_ctx *c, int cls, const T *A, const T *W, float *C, int M, int N, int K, int force_splits, int *splits_out);
+
+template <>
+int run_gemm<float>(sjd_ctx *c, int cls, const float *A, const float *W, float *C, int M, int N, int K, int, int *splits_out) {
+    *splits_out = 1;
+    SJD_LAUNCH(c, cls, launch_gemm_reference<float>(c->stream, A, W, C, M, N, K));
+    return SJD_OK;
+}
+
+template <>
+int run_gemm<bf16_t>(sjd_ctx *c, int cls, const bf16_t *A, const bf16_t *W, float *C, int M, int N, int K, int force_splits,
+                     int *splits_out) {
+    if (c->md.kernel_flags & SJD_KERNELS_REFERENCE) {
+        *splits_out = 1;
+        SJD_LAUNCH(c, cls, launch_gemm_reference<bf16_t>(c->stream, A, W, C, M, N, K));
+        return SJD_OK;
+    }
+    GemmPlan p = plan_gemm_bf16(M, N, K, force_splits);
+    if ((size_t)p.splits * M * N > c->partial_elems && C == c->partial) {
+        // never happens: the workspace is sized with the same plan at create
+        sjd_set_error(c->err, "split-K workspace too small");
+        return SJD_EINVAL;
+    }
+    *splits_out = p.splits;
+    SJD_LAUNCH(c, cls, launch_gemm_bf16(c->stream, p, A, W, C, M, N, K));
+    return SJD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ forward
+// Runs the rows described by c->rm through the model.  Keys and values of active rows are written to
+// their pages; with_head also produces fp32 logits [M][V_s].
+template <typename T> int forward(sjd_ctx *c, bool with_head) {
+    const sjd_model_desc &md = c->md;
+    const int M = c->n_seqs * 2 * c->L, d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
+    const int Nqkv = (H + 2 * Hkv) * hd;
+    hipStream_t st = c->stream;
+    SJD_LAUNCH(c, KC_EMBED, after([&] { embed_kernel<T><<<M, 256, 0, st>>>((const T *)c->tok_emb, c->rm.row_tok, c->x, d); }));
+    int down_splits = 0;
+    for (int l = 0; l < md.n_layers; ++l) {
+        const LayerWeights &lw = c->layers[l];
+        KvPool pool;
+        pool.k = (char *)c->kpool + c->pool_layer_bytes * l;
+        pool.v = (char *)c->vpool + c->pool_layer_bytes * l;
+        pool.page_table = c->page_table;
+        pool.pages_per_seg = c->pps;
+        pool.page_tokens = c->pt;
+
+        SJD_LAUNCH(c, KC_ADDNORM, after([&] {
+                       addnorm_kernel<T><<<M, 256, 0, st>>>(c->x, l == 0 ? nullptr : c->partial, down_splits, M, lw.attn_norm,
+                                                            (T *)c->xn, d, md.rms_eps);
+                   }));
+        int splits = 1;
+        int rc = run_gemm<T>(c, KC_GEMM_QKV, (const T *)c->xn, (const T *)lw.wqkv, c->partial, M, Nqkv, d, 0, &splits);
+        if (rc) return rc;
+        SJD_LAUNCH(c, KC_ROPE_KV, after([&] {
+                       rope_kv_kernel<T><<<M, 256, 0, st>>>(c->partial, splits, M, c->rm.row_tok, c->rm.row_pos, c->rope_cos,
+                                                            c->rope_sin, (T *)c->q, pool, c->L, H, Hkv, hd);
+                   }));
+        SJD_LAUNCH(c, KC_ATTENTION, launch_attention_reference<T>(st, (const T *)c->q, pool, c->rm.row_tok, c->rm.seg_kv,
+                                                                  (T *)c->attn, nullptr, M, c->L, H, Hkv, hd, c->max_visible));
+        rc = run_gemm<T>(c, KC_GEMM_O, (const T *)c->attn, (const T *)lw.wo, c->partial, M, d, H * hd, 0, &splits);
+        if (rc) return rc;
+        SJD_LAUNCH(c, KC_ADDNORM, after([&] {
+                       addnorm_kernel<T><<<M, 256, 0, st>>>(c->x, c->partial, splits, M, lw.mlp_norm, (T *)c->xn, d, md.rms_eps);
+                   }));
+        rc = run_gemm<T>(c, KC_GEMM_GATEUP, (const T *)c->xn, (const T *)lw.wgu, c->partial, M, 2 * F, d, 0, &splits);
+        if (rc) return rc;
+        SJD_LAUNCH(c, KC_SWIGLU, after([&] { swiglu_kernel<T><<<M, 256, 0, st>>>(c->partial, splits, M, (T *)c->h, F); }));
+        rc = run_gemm<T>(c, KC_GEMM_DOWN, (const T *)c->h, (const T *)lw.wdown, c->partial, M, d, F, 0, &down_splits);
+        if (rc) return rc;
+    }
+    if (with_head) {
+        SJD_LAUNCH(c, KC_ADDNORM, after([&] {
+                       addnorm_kernel<T><<<M, 256, 0, st>>>(c->x, c->partial, down_splits, M, c->final_norm, (T *)c->xn, d,
+                                                            md.rms_eps);
+                   }));
+        int splits = 1;
+        int rc = run_gemm<T>(c, KC_GEMM_HEAD, (const T *)c->xn, (const T *)c->lm_head, c->logits, M, c->Vs, d, 1, &splits);
+        if (rc) return rc;
+    }
+    return SJD_OK;
+}
+
+int forward_any(sjd_ctx *c, bool with_head) {
+    return c->md.dtype == SJD_F32 ? forward<float>(c, with_head) : forward<bf16_t>(c, with_head);
+}
+
+// ------------------------------------------------------------------------------------------ create
+template <typename T> int copy_weights(sjd_ctx *c, const sjd_weights *w) {
+    const sjd_model_desc &md = c->md;
+    const int d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
+    hipStream_t st = c->stream;
+    int rc;
+    T *emb;
+    if ((rc = dev_alloc(c, &emb, (size_t)md.vocab * d * sizeof(T), false))) return rc;
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(emb, w->tok_emb, (size_t)md.vocab * d * sizeof(T), hipMemcpyDeviceToDevice, st));
+    c->tok_emb = emb;
+    auto gain = [&](const void *src, float **dst) -> int {
+        int r = dev_alloc(c, dst, (size_t)d * sizeof(float));
+        if (r) return r;
+        to_float_kernel<T><<<ceil_div(d, 256), 256, 0, st>>>((const T *)src, *dst, d);
+        return hipGetLastError() == hipSuccess ? SJD_OK : SJD_EDEVICE;
+    };
+    auto pack = [&](T *dst, const void *src, int N, int K, int row0) -> int {
+        if (!src) { sjd_set_error(c->err, "null weight pointer"); return SJD_EINVAL; }
+        pack_weight_kernel<T><<<1024, 256, 0, st>>>((const T *)src, dst, N, K, row0);
+        return hipGetLastError() == hipSuccess ? SJD_OK : SJD_EDEVICE;
+    };
+    if ((rc = gain(w->final_norm, &c->final_norm))) return rc;
+    T *head;
+    if ((rc = dev_alloc(c, &head, Layout<T>::w_elems(c->Vs, d) * sizeof(T)))) return rc;
+    if ((rc = pack(head, (const T *)w->lm_head + (size_t)md.sample_lo * d, c->Vs, d, 0))) return rc;
+    c->lm_head = head;
+    c->layers.resize(md.n_layers);
+    for (int l = 0; l < md.n_layers; ++l) {
+        LayerWeights &lw = c->layers[l];
+        if (!w->attn_norm[l] || !w->mlp_norm[l]) { sjd_set_error(c->err, "null weight pointer"); return SJD_EINVAL; }
+        if ((rc = gain(w->attn_norm[l], &lw.attn_norm))) return rc;
+        if ((rc = gain(w->mlp_norm[l], &lw.mlp_norm))) return rc;
+        T *qkv, *o, *gu, *down;
+        const int Nqkv = (H + 2 * Hkv) * hd;
+        if ((rc = dev_alloc(c, &qkv, Layout<T>::w_elems(Nqkv, d) * sizeof(T)))) return rc;
+        if ((rc = pack(qkv, w->wq[l], H * hd, d, 0))) return rc;
+        if ((rc = pack(qkv, w->wk[l], Hkv * hd, d, H * hd))) return rc;
+        if ((rc = pack(qkv, w->wv[l], Hkv * hd, d, (H + Hkv) * hd))) return rc;
+        if ((rc = dev_alloc(c, &o, Layout<T>::w_elems(d, H * hd) * sizeof(T)))) return rc;
+        if ((rc = pack(o, w->wo[l], d, H * hd, 0))) return rc;
+        if ((rc = dev_alloc(c, &gu, Layout<T>::w_elems(2 * F, d) * sizeof(T)))) return rc;
+        if ((rc = pack(gu, w->w_gate[l], F, d, 0))) return rc;
+        if ((rc = pack(gu, w->w_up[l], F, d, F))) return rc;
+        if ((rc = dev_alloc(c, &down, Layout<T>::w_elems(d, F) * sizeof(T)))) return rc;
+        if ((rc = pack(down, w->w_down[l], d, F, 0))) return rc;
+        lw.wqkv = qkv; lw.wo = o; lw.wgu = gu; lw.wdown = down;
+    }
+    return SJD_OK;
+}
+
+template <typename T> int alloc_buffers(sjd_ctx *c) {
+    const sjd_model_desc &md = c->md;
+    const int S = c->S, L = c->L, M = S * 2 * L, d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
+    const int Nqkv = (H + 2 * Hkv) * hd;
+    int rc;
+    // KV pages
+    c->pps = ceil_div(md.max_ctx, c->pt);
+    c->n_pages = S * 2 * c->pps;
+    c->pool_layer_bytes = (size_t)c->n_pages * Hkv * c->pt * hd * sizeof(T);
+    if ((rc = dev_alloc(c, &c->kpool, c->pool_layer_bytes * md.n_layers))) return rc;
+    if ((rc = dev_alloc(c, &c->vpool, c->pool_layer_bytes * md.n_layers))) return rc;
+    if ((rc = dev_alloc(c, &c->page_table, (size_t)S * 2 * c->pps * sizeof(int32_t)))) return rc;
+    // workspaces
+    if ((rc = dev_alloc(c, &c->x, (size_t)M * d * sizeof(float)))) return rc;
+    size_t pe = 0;
+    const int shapes[4][2] = {{Nqkv, d}, {d, H * hd}, {2 * F, d}, {d, F}};
+    for (auto &s : shapes) {
+        size_t need = (size_t)M * s[0];
+        if (md.dtype == SJD_BF16 && !(md.kernel_flags & SJD_KERNELS_REFERENCE)) {
+            // worst case over the number of sequences actually decoded (M = n * 2 * L)
+            for (int n = 1; n <= S; ++n) {
+                GemmPlan p = plan_gemm_bf16(n * 2 * L, s[0], s[1], 0);
+                size_t e = (size_t)p.splits * (n * 2 * L) * s[0];
+                if (e > need) need = e;
+            }
+        }
+        if (need > pe) pe = need;
+    }
+    c->partial_elems = pe;
+    if ((rc = dev_alloc(c, &c->partial, pe * sizeof(float)))) return rc;
+    if ((rc = dev_alloc(c, &c->logits, (size_t)M * c->Vs * sizeof(float)))) return rc;
+    if ((rc = dev_alloc(c, &c->xn, Layout<T>::a_elems(M, d) * sizeof(T)))) return rc;
+    if ((rc = dev_alloc(c, &c->attn, Layout<T>::a_elems(M, H * hd) * sizeof(T)))) return rc;
+    if ((rc = dev_alloc(c, &c->h, Layout<T>::a_elems(M, F) * sizeof(T)))) return rc;
+    if ((rc = dev_alloc(c, &c->q, (size_t)S * 2 * H * Layout<T>::q_elems(L, hd) * sizeof(T)))) return rc;
+    return SJD_OK;
+}
+
+int alloc_state(sjd_ctx *c) {
+    const int S = c->S, L = c->L, M = S * 2 * L;
+    int rc;
+    if ((rc = dev_alloc(c, &c->rm.row_tok, (size_t)M * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->rm.row_pos, (size_t)M * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->rm.seg_kv, (size_t)S * 2 * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->rm.seg_n, (size_t)S * 2 * 4))) return rc;
+    DecideState &d = c->ds;
+    d.L = L; d.V = c->Vs; d.lo = c->md.sample_lo; d.max_img = c->md.max_ctx;
+    if ((rc = dev_alloc(c, &d.win_tok, (size_t)S * L * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.anchor, (size_t)S * 2 * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.ref_row, (size_t)S * L * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.n_img, (size_t)S * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.n_image, (size_t)S * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.kv_len, (size_t)S * 2 * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.Le, (size_t)S * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.out_tok, (size_t)S * d.max_img * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.acc_len, (size_t)S * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.cand, (size_t)S * L * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.step, 4))) return rc;
+    for (int b = 0; b < 2; ++b) {
+        if ((rc = dev_alloc(c, &d.e_buf[b], (size_t)S * L * c->Vs * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &d.Z_buf[b], (size_t)S * L * sizeof(uint64_t)))) return rc;
+    }
+    if ((rc = dev_alloc(c, &d.res, (size_t)S * sizeof(sjd_step_result)))) return rc;
+    if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)S * 2 * c->md.max_ctx * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->prompt_len_dev, (size_t)S * 2 * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->prompt_last_dev, (size_t)S * 2 * 4))) return rc;
+    if ((rc = dev_alloc(c, &c->n_image_dev, (size_t)S * 4))) return rc;
+    hipError_t e = hipHostMalloc((void **)&c->res_host, (size_t)S * sizeof(sjd_step_result), hipHostMallocDefault);
+    if (e != hipSuccess) { sjd_set_error(c->err, "hipHostMalloc failed: %s", hipGetErrorString(e)); return SJD_ENOMEM; }
+    return SJD_OK;
+}
+
+int make_rope_tables(sjd_ctx *c) {
+    const int half = c->hd / 2, n = c->md.max_ctx;
+    std::vector<float> cs((size_t)n * half), sn((size_t)n * half);
+    for (int pos = 0; pos < n; ++pos)
+        for (int i = 0; i < half; ++i) {
+            const double angle = (double)pos * pow((double)c->md.rope_theta, -2.0 * i / c->hd);
+            cs[(size_t)pos * half + i] = (float)cos(angle);
+            sn[(size_t)pos * half + i] = (float)sin(angle);
+        }
+    int rc;
+    if ((rc = dev_alloc(c, &c->rope_cos, cs.size() * 4, false))) return rc;
+    if ((rc = dev_alloc(c, &c->rope_sin, sn.size() * 4, false))) return rc;
+    SJD_HIP_TRY(c->err, hipMemcpy(c->rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+    SJD_HIP_TRY(c->err, hipMemcpy(c->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice));
+    return SJD_OK;
+}
+
+int validate_desc(const sjd_model_desc *md, const sjd_weights *w, const sjd_sampling *sp, char *err) {
+    if (!md || !w || !sp) { sjd_set_error(err, "null argument"); return SJD_EINVAL; }
+    if (md->n_layers < 1 || md->d_model < 1 || md->n_heads < 1 || md->n_kv_heads < 1 || md->d_ff < 1 || md->vocab < 1) {
+        sjd_set_error(err, "non-positive model dimension"); return SJD_EINVAL;
+    }
+    if (md->d_model % md->n_heads || md->n_heads % md->n_kv_heads) { sjd_set_error(err, "heads do not divide"); return SJD_EINVAL; }
+    const int hd = md->d_model / md->n_heads;
+    if (hd % 2) { sjd_set_error(err, "odd head dimension"); return SJD_EINVAL; }
+    if (md->sample_lo < 0 || md->sample_hi > md->vocab || md->sample_hi <= md->sample_lo) {
+        sjd_set_error(err, "bad sampled id range"); return SJD_EINVAL;
+    }
+    if (md->dtype != SJD_F32 && md->dtype != SJD_BF16) { sjd_set_error(err, "unknown dtype"); return SJD_EINVAL; }
+    if (md->max_seqs < 1 || md->max_ctx < 2 || md->window < 1 || md->window > 1024) {
+        sjd_set_error(err, "bad capacity (max_seqs >= 1, max_ctx >= 2, 1 <= window <= 1024)"); return SJD_EINVAL;
+    }
+    if (md->kv_page_tokens < 0 || md->kv_page_tokens % 32) { sjd_set_error(err, "kv_page_tokens must be a multiple of 32"); return SJD_EINVAL; }
+    if (md->dtype == SJD_BF16 && (hd % 32 || md->d_model % 16 || md->d_ff % 16)) {
+        sjd_set_error(err, "bf16 needs head_dim %% 32 == 0, d_model %% 16 == 0, d_ff %% 16 == 0"); return SJD_EINVAL;
+    }
+    if (!(md->rms_eps > 0.0f) || !(md->rope_theta > 0.0f)) { sjd_set_error(err, "bad rms_eps / rope_theta"); return SJD_EINVAL; }
+    if (sp->top_k < 1 || !(sp->temperature > 0.0f) || sp->init_mode != 0 || sp->reuse_tau != sp->reuse_tau || sp->reuse_tau < 0.0f) {
+        sjd_set_error(err, "bad sampling parameters (top_k >= 1, temperature > 0, tau >= 0, init_mode 0)"); return SJD_EINVAL;
+    }
+    if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm ||
+        !w->w_gate || !w->w_up || !w->w_down) {
+        sjd_set_error(err, "null weight pointer"); return SJD_EINVAL;
+    }
+    return SJD_OK;
+}
+
+int run_decide(sjd_ctx *c) {
+    SJD_LAUNCH(c, KC_SAMPLE_ROWS, launch_sample_rows(c->stream, c->ds, c->sp, c->logits, c->n_seqs));
+    SJD_LAUNCH(c, KC_VERIFY, launch_verify(c->stream, c->ds, c->sp, c->n_seqs));
+    SJD_LAUNCH(c, KC_DRAW, launch_draw(c->stream, c->ds, c->sp, c->n_seqs));
+    SJD_LAUNCH(c, KC_COMMIT, launch_commit(c->stream, c->ds, c->sp, c->n_seqs));
+    return SJD_OK;
+}
+
+int finish_step(sjd_ctx *c, sjd_step_result *out) {
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->res_host, c->ds.res, (size_t)c->n_seqs * sizeof(sjd_step_result), hipMemcpyDeviceToHost,
+                                       c->stream));
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    trace_collect(c);
+    bool all = true;
+    for (int s = 0; s < c->n_seqs; ++s) {
+        out[s] = c->res_host[s];
+        all = all && out[s].done;
+    }
+    c->all_done = all;
+    return SJD_OK;
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char *sjd_last_error(const sjd_ctx *ctx) { return ctx ? ctx->err : g_create_error; }
+
+void sjd_destroy(sjd_ctx *c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->allocations) (void)hipFree(p);
+    if (c->res_host) (void)hipHostFree(c->res_host);
+    for (hipEvent_t e : c->tracer.pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd_sampling *sampling, void *hip_stream,
+               sjd_ctx **out) {
+    if (!out) { sjd_set_error(g_create_error, "null output pointer"); return SJD_EINVAL; }
+    *out = nullptr;
+    int rc = validate_desc(desc, weights, sampling, g_create_error);
+    if (rc) return rc;
+    sjd_ctx *c = new (std::nothrow) sjd_ctx();
+    if (!c) { sjd_set_error(g_create_error, "out of host memory"); return SJD_ENOMEM; }
+    c->md = *desc;
+    c->sampling = *sampling;
+    c->stream = (hipStream_t)hip_stream;
+    c->hd = desc->d_model / desc->n_heads;
+    c->Vs = desc->sample_hi - desc->sample_lo;
+    c->L = desc->window;
+    c->S = desc->max_seqs;
+    c->pt = desc->kv_page_tokens ? desc->kv_page_tokens : 64;
+    c->md.kv_page_tokens = c->pt;
+    c->max_visible = desc->max_ctx + 1;
+    c->sp.cfg_scale = sampling->cfg_scale;
+    c->sp.inv_temperature = 1.0f / sampling->temperature;
+    c->sp.tau = sampling->reuse_tau;
+    c->sp.top_k = sampling->top_k;
+    c->sp.seed = sampling->seed;
+    const bool f32 = desc->dtype == SJD_F32;
+    rc = f32 ? copy_weights<float>(c, weights) : copy_weights<bf16_t>(c, weights);
+    if (!rc) rc = f32 ? alloc_buffers<float>(c) : alloc_buffers<bf16_t>(c);
+    if (!rc) rc = alloc_state(c);
+    if (!rc) rc = make_rope_tables(c);
+    if (!rc && hipStreamSynchronize(c->stream) != hipSuccess) {
+        sjd_set_error(c->err, "device error while copying the weights: %s", hipGetErrorString(hipGetLastError()));
+        rc = SJD_EDEVICE;
+    }
+    if (rc) {
+        memcpy(g_create_error, c->err, sizeof g_create_error);
+        sjd_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return SJD_OK;
+}
+
+int sjd_prefill(sjd_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, const int32_t *cond_len,
+                const int32_t *const *uncond_ids, const int32_t *uncond_len, const int32_t *n_image_tokens) {
+    if (!c) return SJD_EINVAL;
+    if (!cond_ids || !cond_len || !uncond_ids || !uncond_len || !n_image_tokens || n_seqs < 1) {
+        sjd_set_error(c->err, "null argument or n_seqs < 1");
+        return SJD_EINVAL;
+    }
+    if (n_seqs > c->S) { sjd_set_error(c->err, "n_seqs %d > max_seqs %d", n_seqs, c->S); return SJD_ECAPACITY; }
+    int max_prompt = 1;
+    for (int s = 0; s < n_seqs; ++s) {
+        if (!cond_ids[s] || !uncond_ids[s] || cond_len[s] < 1 || uncond_len[s] < 1 || n_image_tokens[s] < 1) {
+            sjd_set_error(c->err, "sequence %d: null prompt, empty prompt or no image tokens", s);
+            return SJD_EINVAL;
+        }
+        if (cond_len[s] + n_image_tokens[s] > c->md.max_ctx || uncond_len[s] + n_image_tokens[s] > c->md.max_ctx) {
+            sjd_set_error(c->err, "sequence %d: prompt + image tokens exceed max_ctx %d", s, c->md.max_ctx);
+            return SJD_ECAPACITY;
+        }
+        for (int i = 0; i < cond_len[s]; ++i)
+            if (cond_ids[s][i] < 0 || cond_ids[s][i] >= c->md.vocab) { sjd_set_error(c->err, "token id outside the vocabulary"); return SJD_EINVAL; }
+        for (int i = 0; i < uncond_len[s]; ++i)
+            if (uncond_ids[s][i] < 0 || uncond_ids[s][i] >= c->md.vocab) { sjd_set_error(c->err, "token id outside the vocabulary"); return SJD_EINVAL; }
+        if (cond_len[s] > max_prompt) max_prompt = cond_len[s];
+        if (uncond_len[s] > max_prompt) max_prompt = uncond_len[s];
+    }
+    c->prefilled = false;
+    c->n_seqs = n_seqs;
+    const int L = c->L;
+    // host staging
+    std::vector<int32_t> prompt((size_t)n_seqs * 2 * max_prompt, 0), plen((size_t)n_seqs * 2), plast((size_t)n_seqs * 2);
+    std::vector<int32_t> table((size_t)c->S * 2 * c->pps, 0);
+    // Pages are handed out round-robin over the segments, so that the pages of one segment are not
+    // contiguous in the pool; a segment takes only the pages its prompt + image need.
+    {
+        std::vector<int> need((size_t)n_seqs * 2), got((size_t)n_seqs * 2, 0);
+        int next = 0, pending = 0;
+        for (int s = 0; s < n_seqs; ++s) {
+            need[s * 2] = ceil_div(cond_len[s] + n_image_tokens[s], c->pt);
+            need[s * 2 + 1] = ceil_div(uncond_len[s] + n_image_tokens[s], c->pt);
+            pending += need[s * 2] + need[s * 2 + 1];
+        }
+        if (pending > c->n_pages) { sjd_set_error(c->err, "KV page pool exhausted"); return SJD_ECAPACITY; }
+        while (pending > 0)
+            for (int seg = 0; seg < n_seqs * 2; ++seg)
+                if (got[seg] < need[seg]) { table[(size_t)seg * c->pps + got[seg]++] = next++; --pending; }
+    }
+    for (int s = 0; s < n_seqs; ++s) {
+        const int32_t *ids[2] = {cond_ids[s], uncond_ids[s]};
+        const int len[2] = {cond_len[s], uncond_len[s]};
+        for (int b = 0; b < 2; ++b) {
+            memcpy(&prompt[((size_t)s * 2 + b) * max_prompt], ids[b], sizeof(int32_t) * len[b]);
+            plen[s * 2 + b] = len[b];
+            plast[s * 2 + b] = ids[b][len[b] - 1];
+        }
+    }
+    hipStream_t st = c->stream;
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->prompt_dev, prompt.data(), prompt.size() * 4, hipMemcpyHostToDevice, st));
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->prompt_len_dev, plen.data(), plen.size() * 4, hipMemcpyHostToDevice, st));
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->prompt_last_dev, plast.data(), plast.size() * 4, hipMemcpyHostToDevice, st));
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->n_image_dev, n_image_tokens, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->page_table, table.data(), table.size() * 4, hipMemcpyHostToDevice, st));
+    const int chunks = ceil_div(max_prompt - 1, L);
+    for (int ch = 0; ch < chunks; ++ch) {
+        SJD_LAUNCH(c, KC_STAGE, launch_stage_prompt(st, c->rm, c->prompt_dev, c->prompt_len_dev, max_prompt, ch, L, n_seqs));
+        int rc = forward_any(c, false);
+        if (rc) return rc;
+    }
+    SJD_LAUNCH(c, KC_STAGE, launch_init_window(st, c->ds, c->sp, n_seqs, c->S, c->prompt_last_dev, c->prompt_len_dev, c->n_image_dev));
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(st));
+    trace_collect(c);
+    c->prefilled = true;
+    c->all_done = false;
+    return SJD_OK;
+}
+
+int sjd_step(sjd_ctx *c, sjd_step_result *out) {
+    if (!c) return SJD_EINVAL;
+    if (!out) { sjd_set_error(c->err, "null result pointer"); return SJD_EINVAL; }
+    if (!c->prefilled) { sjd_set_error(c->err, "sjd_step before sjd_prefill"); return SJD_ESTATE; }
+    SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
+    int rc = forward_any(c, true);
+    if (rc) return rc;
+    if ((rc = run_decide(c))) return rc;
+    return finish_step(c, out);
+}
+
+int sjd_debug_step_from_logits(sjd_ctx *c, const float *logits_host, sjd_step_result *out) {
+    if (!c) return SJD_EINVAL;
+    if (!out || !logits_host) { sjd_set_error(c->err, "null pointer"); return SJD_EINVAL; }
+    if (!c->prefilled) { sjd_set_error(c->err, "step before sjd_prefill"); return SJD_ESTATE; }
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(c->logits, logits_host, (size_t)c->n_seqs * 2 * c->L * c->Vs * sizeof(float),
+                                       hipMemcpyHostToDevice, c->stream));
+    SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
+    int rc = run_decide(c);
+    if (rc) return rc;
+    return finish_step(c, out);
+}
+
+int sjd_debug_copy_logits(sjd_ctx *c, float *dst_host) {
+    if (!c || !dst_host) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "no step yet"); return SJD_ESTATE; }
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    SJD_HIP_TRY(c->err, hipMemcpy(dst_host, c->logits, (size_t)c->n_seqs * 2 * c->L * c->Vs * sizeof(float), hipMemcpyDeviceToHost));
+    return SJD_OK;
+}
+
+int sjd_get_tokens(sjd_ctx *c, int32_t seq, int32_t *dst, int32_t cap, int32_t *n_out) {
+    if (!c || !n_out) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "no prefill yet"); return SJD_ESTATE; }
+    if (seq < 0 || seq >= c->n_seqs || cap < 0 || (cap > 0 && !dst)) { sjd_set_error(c->err, "bad sequence index or buffer"); return SJD_EINVAL; }
+    int32_t n = 0;
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    SJD_HIP_TRY(c->err, hipMemcpy(&n, c->ds.n_img + seq, 4, hipMemcpyDeviceToHost));
+    const int32_t k = n < cap ? n : cap;
+    if (k > 0) SJD_HIP_TRY(c->err, hipMemcpy(dst, c->ds.out_tok + (size_t)seq * c->ds.max_img, (size_t)k * 4, hipMemcpyDeviceToHost));
+    *n_out = n;
+    return SJD_OK;
+}
+
+int sjd_get_window(sjd_ctx *c, int32_t seq, int32_t *tokens, int32_t *ref_rows, int32_t *n_slots) {
+    if (!c || !tokens || !ref_rows || !n_slots) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "no prefill yet"); return SJD_ESTATE; }
+    if (seq < 0 || seq >= c->n_seqs) { sjd_set_error(c->err, "bad sequence index"); return SJD_EINVAL; }
+    const int L = c->L;
+    int32_t le = 0;
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    SJD_HIP_TRY(c->err, hipMemcpy(tokens, c->ds.win_tok + (size_t)seq * L, (size_t)L * 4, hipMemcpyDeviceToHost));
+    SJD_HIP_TRY(c->err, hipMemcpy(ref_rows, c->ds.ref_row + (size_t)seq * L, (size_t)L * 4, hipMemcpyDeviceToHost));
+    SJD_HIP_TRY(c->err, hipMemcpy(tokens, c->ds.anchor + (size_t)seq * 2, 4, hipMemcpyDeviceToHost));
+    SJD_HIP_TRY(c->err, hipMemcpy(&le, c->ds.Le + seq, 4, hipMemcpyDeviceToHost));
+    ref_rows[0] = -1;
+    *n_slots = le;
+    return SJD_OK;
+}
+
+int sjd_trace_enable(sjd_ctx *c, int32_t on) {
+    if (!c) return SJD_EINVAL;
+    c->tracer.on = on != 0;
+    return SJD_OK;
+}
+int sjd_trace_reset(sjd_ctx *c) {
+    if (!c) return SJD_EINVAL;
+    for (int i = 0; i < KC_COUNT; ++i) { c->tracer.launches[i] = 0; c->tracer.total_ms[i] = 0.0; }
+    return SJD_OK;
+}
+int sjd_trace_read(sjd_ctx *c, sjd_trace_entry *dst, int32_t cap, int32_t *n_out) {
+    if (!c || !n_out || (cap > 0 && !dst)) return SJD_EINVAL;
+    for (int i = 0; i < KC_COUNT && i < cap; ++i) {
+        dst[i].name = kKernelClassName[i];
+        dst[i].launches = c->tracer.launches[i];
+        dst[i].total_ms = c->tracer.total_ms[i];
+    }
+    *n_out = KC_COUNT;
+    return SJD_OK;
+}
+
+}  // extern "C"
+
+#include "sjd_ops.hip.h"

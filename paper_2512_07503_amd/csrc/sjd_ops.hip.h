@@ -1,0 +1,181 @@
+// Single-operation entry points of include/sjd.h (kernel-level tests and microbenchmarks).
+// Included at the end of sjd_api.hip.
+#pragma once
+
+namespace {
+
+struct Scratch {
+    std::vector<void *> ptrs;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    ~Scratch() {
+        for (void *p : ptrs) (void)hipFree(p);
+        if (ev0) (void)hipEventDestroy(ev0);
+        if (ev1) (void)hipEventDestroy(ev1);
+    }
+    template <typename P> bool alloc(P **out, size_t bytes, hipStream_t st) {
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes ? bytes : 16) != hipSuccess) return false;
+        ptrs.push_back(p);
+        if (hipMemsetAsync(p, 0, bytes ? bytes : 16, st) != hipSuccess) return false;
+        *out = reinterpret_cast<P *>(p);
+        return true;
+    }
+    bool events() { return hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess; }
+};
+
+#define OP_TRY(expr)                                                                                  \
+    do {                                                                                              \
+        hipError_t e__ = (expr);                                                                      \
+        if (e__ != hipSuccess) {                                                                      \
+            sjd_set_error(g_create_error, "%s failed: %s", #expr, hipGetErrorString(e__));            \
+            return SJD_EDEVICE;                                                                       \
+        }                                                                                             \
+    } while (0)
+
+template <typename T>
+int op_gemm(hipStream_t st, int flags, const void *A, const void *W, float *C, int M, int N, int K, int splits, int repeat,
+            float *avg_ms) {
+    Scratch s;
+    T *Ap, *Wp;
+    float *partial;
+    const bool ref = std::is_same<T, float>::value || (flags & SJD_KERNELS_REFERENCE);
+    GemmPlan plan = plan_gemm_bf16(M, N, K, splits);
+    const int n_splits = ref ? 1 : plan.splits;
+    if (!s.alloc(&Ap, Layout<T>::a_elems(M, K) * sizeof(T), st) || !s.alloc(&Wp, Layout<T>::w_elems(N, K) * sizeof(T), st) ||
+        !s.alloc(&partial, (size_t)n_splits * M * N * sizeof(float), st) || !s.events()) {
+        sjd_set_error(g_create_error, "allocation failed");
+        return SJD_ENOMEM;
+    }
+    pack_act_kernel<T><<<512, 256, 0, st>>>((const T *)A, Ap, M, K);
+    OP_TRY(hipGetLastError());
+    pack_weight_kernel<T><<<1024, 256, 0, st>>>((const T *)W, Wp, N, K, 0);
+    OP_TRY(hipGetLastError());
+    OP_TRY(hipEventRecord(s.ev0, st));
+    for (int r = 0; r < repeat; ++r) {
+        if (ref) OP_TRY(launch_gemm_reference<T>(st, Ap, Wp, partial, M, N, K));
+        else OP_TRY(launch_gemm_bf16(st, plan, (const bf16_t *)Ap, (const bf16_t *)Wp, partial, M, N, K));
+    }
+    OP_TRY(hipEventRecord(s.ev1, st));
+    reduce_partials_kernel<<<(unsigned)ceil_div_sz((size_t)M * N, 256), 256, 0, st>>>(partial, n_splits, (size_t)M * N, C);
+    OP_TRY(hipGetLastError());
+    OP_TRY(hipStreamSynchronize(st));
+    if (avg_ms) {
+        float ms = 0.0f;
+        OP_TRY(hipEventElapsedTime(&ms, s.ev0, s.ev1));
+        *avg_ms = ms / repeat;
+    }
+    return SJD_OK;
+}
+
+template <typename T>
+int op_attention(hipStream_t st, int flags, const void *q, const void *k, const void *v, float *out, int n, int ctx, int H,
+                 int Hkv, int hd, int pt, int repeat, float *avg_ms) {
+    (void)flags;
+    Scratch s;
+    const int n_tok = ctx + n, pages = ceil_div(n_tok, pt);
+    KvPool pool;
+    T *qp;
+    int32_t *table, *row_tok, *seg_kv;
+    const size_t pool_bytes = (size_t)pages * Hkv * pt * hd * sizeof(T);
+    if (!s.alloc(&pool.k, pool_bytes, st) || !s.alloc(&pool.v, pool_bytes, st) || !s.alloc(&table, (size_t)pages * 4, st) ||
+        !s.alloc(&row_tok, (size_t)n * 4, st) || !s.alloc(&seg_kv, 4, st) ||
+        !s.alloc(&qp, (size_t)H * Layout<T>::q_elems(n, hd) * sizeof(T), st) || !s.events()) {
+        sjd_set_error(g_create_error, "allocation failed");
+        return SJD_ENOMEM;
+    }
+    std::vector<int32_t> tab(pages);
+    for (int i = 0; i < pages; ++i) tab[i] = pages - 1 - i;  // pages deliberately out of order
+    OP_TRY(hipMemcpyAsync(table, tab.data(), (size_t)pages * 4, hipMemcpyHostToDevice, st));
+    OP_TRY(hipMemcpyAsync(seg_kv, &ctx, 4, hipMemcpyHostToDevice, st));
+    OP_TRY(hipStreamSynchronize(st));
+    pool.page_table = table;
+    pool.pages_per_seg = pages;
+    pool.page_tokens = pt;
+    pack_kv_kernel<T><<<512, 256, 0, st>>>((const T *)k, (const T *)v, pool, n_tok, Hkv, hd);
+    OP_TRY(hipGetLastError());
+    pack_q_kernel<T><<<64, 256, 0, st>>>((const T *)q, qp, n, H, hd, n);
+    OP_TRY(hipGetLastError());
+    OP_TRY(hipEventRecord(s.ev0, st));
+    for (int r = 0; r < repeat; ++r)
+        OP_TRY(launch_attention_reference<T>(st, qp, pool, row_tok, seg_kv, (T *)nullptr, out, n, n, H, Hkv, hd, n_tok + 1));
+    OP_TRY(hipEventRecord(s.ev1, st));
+    OP_TRY(hipStreamSynchronize(st));
+    if (avg_ms) {
+        float ms = 0.0f;
+        OP_TRY(hipEventElapsedTime(&ms, s.ev0, s.ev1));
+        *avg_ms = ms / repeat;
+    }
+    return SJD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sjd_op_gemm(void *hip_stream, int32_t dtype, int32_t flags, const void *A, const void *W, float *C, int32_t M, int32_t N,
+                int32_t K, int32_t splits, int32_t repeat, float *avg_ms) {
+    if (!A || !W || !C || M < 1 || N < 1 || K < 1 || repeat < 1) { sjd_set_error(g_create_error, "bad argument"); return SJD_EINVAL; }
+    if (dtype == SJD_F32) return op_gemm<float>((hipStream_t)hip_stream, flags, A, W, C, M, N, K, splits, repeat, avg_ms);
+    if (dtype == SJD_BF16) {
+        if (K % 16) { sjd_set_error(g_create_error, "bf16 GEMM needs K %% 16 == 0"); return SJD_EINVAL; }
+        return op_gemm<bf16_t>((hipStream_t)hip_stream, flags, A, W, C, M, N, K, splits, repeat, avg_ms);
+    }
+    sjd_set_error(g_create_error, "unknown dtype");
+    return SJD_EINVAL;
+}
+
+int sjd_op_window_attention(void *hip_stream, int32_t dtype, int32_t flags, const void *q, const void *k, const void *v,
+                            float *out, int32_t n, int32_t ctx, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
+                            int32_t page_tokens, int32_t repeat, float *avg_ms) {
+    if (!q || !k || !v || !out || n < 1 || ctx < 0 || n_heads < 1 || n_kv_heads < 1 || n_heads % n_kv_heads || head_dim < 2 ||
+        head_dim % 2 || page_tokens < 32 || page_tokens % 32 || repeat < 1) {
+        sjd_set_error(g_create_error, "bad argument");
+        return SJD_EINVAL;
+    }
+    if (dtype == SJD_F32)
+        return op_attention<float>((hipStream_t)hip_stream, flags, q, k, v, out, n, ctx, n_heads, n_kv_heads, head_dim, page_tokens,
+                                   repeat, avg_ms);
+    if (dtype == SJD_BF16) {
+        if (head_dim % 32) { sjd_set_error(g_create_error, "bf16 attention needs head_dim %% 32 == 0"); return SJD_EINVAL; }
+        return op_attention<bf16_t>((hipStream_t)hip_stream, flags, q, k, v, out, n, ctx, n_heads, n_kv_heads, head_dim,
+                                    page_tokens, repeat, avg_ms);
+    }
+    sjd_set_error(g_create_error, "unknown dtype");
+    return SJD_EINVAL;
+}
+
+int sjd_op_sampling_rows(void *hip_stream, const float *logits_c, const float *logits_u, float *e, uint64_t *Z, int32_t rows,
+                         int32_t V, float cfg_scale, float temperature, int32_t top_k, int32_t repeat, float *avg_ms) {
+    if (!logits_c || !logits_u || !e || !Z || rows < 1 || V < 1 || top_k < 1 || !(temperature > 0.0f) || repeat < 1) {
+        sjd_set_error(g_create_error, "bad argument");
+        return SJD_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    Scratch s;
+    if (!s.events()) return SJD_ENOMEM;
+    SamplingParams sp;
+    sp.cfg_scale = cfg_scale;
+    sp.inv_temperature = 1.0f / temperature;
+    sp.tau = 0.0f;
+    sp.top_k = top_k;
+    sp.seed = 0;
+    OP_TRY(hipEventRecord(s.ev0, st));
+    for (int r = 0; r < repeat; ++r) OP_TRY(launch_sampling_rows_plain(st, logits_c, logits_u, e, Z, rows, V, sp));
+    OP_TRY(hipEventRecord(s.ev1, st));
+    OP_TRY(hipStreamSynchronize(st));
+    if (avg_ms) {
+        float ms = 0.0f;
+        OP_TRY(hipEventElapsedTime(&ms, s.ev0, s.ev1));
+        *avg_ms = ms / repeat;
+    }
+    return SJD_OK;
+}
+
+int sjd_op_philox(void *hip_stream, uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int32_t n) {
+    if (!out || n < 1) { sjd_set_error(g_create_error, "bad argument"); return SJD_EINVAL; }
+    OP_TRY(launch_philox_fill((hipStream_t)hip_stream, seed, row, seq, out, n));
+    OP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+    return SJD_OK;
+}
+
+}  // extern "C"

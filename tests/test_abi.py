@@ -1,0 +1,72 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol include/sjd.h declares, and rejects bad
+arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sjd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sjd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2512_07503_amd as sjd
+    L = sjd.lib()
+    names = _declared()
+    assert {"sjd_create", "sjd_prefill", "sjd_step", "sjd_destroy"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_create_rejects_bad_arguments_on_the_host():
+    import paper_2512_07503_amd as sjd
+    from paper_2512_07503_amd.binding import ModelDesc, Weights, Sampling
+    L = sjd.lib()
+    ctx = C.c_void_p()
+    good = dict(n_layers=1, d_model=64, n_heads=2, n_kv_heads=1, d_ff=64, vocab=100, sample_lo=0, sample_hi=100,
+                rms_eps=1e-5, rope_theta=1e4, dtype=1, max_seqs=1, max_ctx=64, window=4, kv_page_tokens=64, kernel_flags=0)
+    arr = (C.c_void_p * 1)(1)
+    w = Weights(1, 1, 1, *[C.cast(arr, C.POINTER(C.c_void_p))] * 9)
+    sp = Sampling(3.0, 1.0, 10, 0.5, 0, 0)
+    assert L.sjd_create(None, C.byref(w), C.byref(sp), None, C.byref(ctx)) == sjd.binding.EINVAL
+    assert L.sjd_create(C.byref(ModelDesc(**good)), C.byref(w), C.byref(sp), None, None) == sjd.binding.EINVAL
+    bad_cases = [dict(n_heads=3), dict(n_kv_heads=0), dict(sample_hi=101), dict(sample_lo=100), dict(dtype=7),
+                 dict(window=0), dict(window=5000), dict(max_seqs=0), dict(kv_page_tokens=48), dict(d_model=40, n_heads=2),
+                 dict(d_ff=24), dict(rms_eps=0.0)]
+    for change in bad_cases:
+        md = ModelDesc(**{**good, **change})
+        assert L.sjd_create(C.byref(md), C.byref(w), C.byref(sp), None, C.byref(ctx)) == sjd.binding.EINVAL, change
+        assert not ctx.value
+        assert L.sjd_last_error(None)
+    for bad_sp in (Sampling(3.0, 1.0, 0, 0.5, 0, 0), Sampling(3.0, 0.0, 5, 0.5, 0, 0), Sampling(3.0, 1.0, 5, -1.0, 0, 0),
+                   Sampling(3.0, 1.0, 5, 0.5, 0, 3), Sampling(3.0, 1.0, 5, float("nan"), 0, 0)):
+        assert L.sjd_create(C.byref(ModelDesc(**good)), C.byref(w), C.byref(bad_sp), None, C.byref(ctx)) == sjd.binding.EINVAL
+    w0 = Weights(0, 1, 1, *[C.cast(arr, C.POINTER(C.c_void_p))] * 9)
+    assert L.sjd_create(C.byref(ModelDesc(**good)), C.byref(w0), C.byref(sp), None, C.byref(ctx)) == sjd.binding.EINVAL
+
+
+def test_null_context_calls_are_errors_not_crashes():
+    import paper_2512_07503_amd as sjd
+    L = sjd.lib()
+    assert L.sjd_step(None, None) == sjd.binding.EINVAL
+    assert L.sjd_prefill(None, 1, None, None, None, None, None) == sjd.binding.EINVAL
+    assert L.sjd_get_tokens(None, 0, None, 0, None) == sjd.binding.EINVAL
+    assert L.sjd_trace_enable(None, 1) == sjd.binding.EINVAL
+    L.sjd_destroy(None)
+    assert L.sjd_op_gemm(None, 1, 0, None, None, None, 1, 1, 16, 0, 1, None) == sjd.binding.EINVAL
+    assert L.sjd_op_philox(None, 0, 0, 0, None, 4) == sjd.binding.EINVAL
+
+
+def test_the_product_does_not_reach_into_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2512_07503_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

@@ -1,0 +1,78 @@
+"""Decision stage on the GPU (sampling distribution, verification, residual / refresh draws, window update) against
+the oracle on identical fp32 logits and identical Philox counters: token ids, accept counts, rejection index and the
+whole next window must be bit-exact at every step."""
+import numpy as np
+import pytest
+
+import workload
+from helpers import make_pair, assert_same_state
+
+pytestmark = pytest.mark.gpu
+
+
+def _drive(oracle, cfg_name, n_steps, window, n_image, n_seqs, top_k, tau, seed, scale, drift, prompt_len=4):
+    cfg = workload.get_config(cfg_name)
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=window, n_image=n_image, prompt_len=prompt_len, n_seqs=n_seqs,
+                                          top_k=top_k, tau=tau, seed=seed, n_layers=1)
+    S, L, Vs = n_seqs, window, o.Vs
+    rng = np.random.default_rng(seed + 99)
+    Nmax = max(n_img)
+    base = (rng.standard_normal((S, 2, Nmax + L, Vs)) * scale).astype(np.float32)   # a row per absolute image position
+    done_img = [0] * S
+    stats = dict(acc=0, steps=0, rej=0)
+    for step in range(n_steps):
+        lg = np.zeros((S, 2, L, Vs), dtype=np.float32)
+        for s in range(S):
+            lg[s] = base[s, :, done_img[s]: done_img[s] + L] + (rng.standard_normal((2, L, Vs)) * drift).astype(np.float32)
+        ro = o.step_from_logits(lg)
+        rg = g.step_from_logits(lg)
+        assert ro == rg, (step, ro, rg)
+        assert_same_state(o, g, S, where=f"step {step}")
+        for s in range(S):
+            done_img[s] += ro[s]["n_finalized"]
+            stats["acc"] += ro[s]["n_accepted"]
+            stats["rej"] += ro[s]["reject_index"] >= 0
+        stats["steps"] += 1
+        if all(r["done"] for r in ro):
+            break
+    return stats
+
+
+@pytest.mark.parametrize("name,L,N,S,K,tau,seed,scale,drift", [
+    ("small_f32", 8, 60, 1, 50, 0.5, 1, 2.0, 0.3),
+    ("small_f32", 8, 60, 2, 50, float("inf"), 2, 2.0, 0.3),
+    ("small_f32", 16, 33, 3, 512, 0.0, 3, 1.0, 0.1),
+    ("small_sub", 5, 30, 3, 40, 0.5, 4, 2.0, 0.5),
+    ("small_f32", 1, 12, 1, 50, 0.5, 5, 2.0, 0.3),
+    ("small_f32", 2, 9, 2, 1, 0.5, 6, 2.0, 0.0),
+    ("small_f32", 70, 200, 1, 50, 0.5, 7, 1.5, 0.05),
+])
+def test_decisions_bit_exact_small(oracle, name, L, N, S, K, tau, seed, scale, drift):
+    st = _drive(oracle, name, 400, L, N, S, K, tau, seed, scale, drift)
+    assert st["steps"] > 0
+
+
+def test_decisions_bit_exact_cfg0_shape(oracle):
+    """V_s = 4096, K = 256, L = 16 as in the first benchmark configuration, 256 image tokens, to completion."""
+    st = _drive(oracle, "cfg0", 400, 16, 256, 1, 256, 0.5, 0, 3.0, 0.15)
+    assert st["acc"] > 0 and st["rej"] > 0
+
+
+def test_decisions_bit_exact_large_vocab(oracle):
+    """V_s = 65536, K = 2000, L = 32 (the 7B-shaped configurations), two sequences, a few steps."""
+    cfg = workload.get_config("cfg2")
+    cfg["arch"] = dict(cfg["arch"], d_model=64, n_heads=2, n_kv_heads=2, d_ff=64)   # only V_s matters here
+    import helpers
+    o, g, *_ = helpers.make_pair(oracle, cfg, window=32, n_image=80, prompt_len=3, n_seqs=2, n_layers=1)
+    rng = np.random.default_rng(5)
+    Vs = o.Vs
+    base = (rng.standard_normal((2, 2, 120, Vs)) * 2.5).astype(np.float32)
+    pos = [0, 0]
+    for step in range(6):
+        lg = np.stack([base[s, :, pos[s]: pos[s] + 32] + (rng.standard_normal((2, 32, Vs)) * 0.1).astype(np.float32)
+                       for s in range(2)])
+        ro, rg = o.step_from_logits(lg), g.step_from_logits(lg)
+        assert ro == rg, (step, ro, rg)
+        assert_same_state(o, g, 2, where=f"step {step}")
+        for s in range(2):
+            pos[s] += ro[s]["n_finalized"]

@@ -1,0 +1,113 @@
+"""Whole decoding path on the GPU against the oracle: forward logits within tolerance at every step, decisions
+bit-exact on the GPU's own logits, and the whole token sequence identical in fp32 mode.
+
+Tolerances (the benchmark spec): fp32 mode max-abs 1e-4 on the logits; bf16 mode 3e-2 of the row's largest
+|logit| (weights are identical bf16 values on both sides; the GPU also rounds GEMM inputs and the KV cache to bf16)."""
+import numpy as np
+import pytest
+
+import workload
+from helpers import make_pair, assert_same_state, logits_error
+
+pytestmark = pytest.mark.gpu
+
+
+def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
+    """Each step: the oracle's own forward for the current window is compared with the GPU's logits; then the oracle
+    decides on the GPU's logits (so both stay on one trajectory) and every decision must equal the GPU's."""
+    worst = (0.0, 0.0)
+    steps = 0
+    for step in range(n_steps):
+        les = [g.window(s)[2] for s in range(S)]
+        want = o.peek_logits()
+        rg = g.step()
+        glog = g.logits()
+        err = logits_error(glog, want, les)
+        worst = (max(worst[0], err[0]), max(worst[1], err[1]))
+        if tol_abs is not None:
+            assert err[0] <= tol_abs, (step, err)
+        if tol_rel is not None:
+            assert err[1] <= tol_rel, (step, err)
+        ro = o.step_from_logits(glog)
+        assert ro == rg, (step, ro, rg)
+        assert_same_state(o, g, S, where=f"step {step}")
+        steps += 1
+        if all(r["done"] for r in rg):
+            break
+    return worst, steps
+
+
+@pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1)])
+def test_small_models_step_by_step(oracle, name, flags):
+    cfg = workload.get_config(name)
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, kernel_flags=flags, head_alpha=6.0, std=0.08, random_gains=True)
+    f32 = cfg["dtype"] == "f32"
+    worst, steps = _lockstep(o, g, cfg["n_seqs"], 200, tol_abs=1e-4 if f32 else None, tol_rel=None if f32 else 3e-2)
+    for s in range(cfg["n_seqs"]):
+        assert len(g.tokens(s)) == n_img[s]
+    print(name, "steps", steps, "worst logits error abs/rel:", worst)
+
+
+def test_cfg0_whole_sequence_identity(oracle):
+    """configs[0] in fp32: the GPU decode and the oracle decode, each on its own forward, give the same 256 tokens."""
+    cfg = workload.get_config("cfg0")
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg)
+    ho = o.decode()
+    hg = g.decode()
+    to, tg = o.tokens(), g.tokens()
+    if not np.array_equal(to, tg):
+        n = min(len(to), len(tg))
+        diff = np.flatnonzero(to[:n] != tg[:n])
+        first = int(diff[0]) if len(diff) else n
+        pytest.fail(f"token sequences differ from image token {first}: oracle {to[first:first+4]} gpu {tg[first:first+4]}")
+    assert ho == hg
+    assert len(to) == 256
+    print("cfg0 forwards per image:", len(hg), "tokens/step:", 256 / len(hg))
+
+
+def test_cfg0_logits_and_decisions_every_step(oracle):
+    cfg = workload.get_config("cfg0")
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg)
+    worst, steps = _lockstep(o, g, 1, 400, tol_abs=1e-4)
+    assert len(g.tokens()) == 256
+    print("cfg0 steps", steps, "worst logits error abs/rel:", worst)
+
+
+@pytest.mark.parametrize("name,layers,prompt,steps,S", [("cfg1", 36, 24, 3, 1), ("cfg1", 2, 120, 40, 1),
+                                                        ("cfg2", 2, 64, 3, 1), ("cfg3", 2, 64, 3, 1), ("cfg4", 2, 64, 3, 3)])
+def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S):
+    """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
+    sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
+    cfg = workload.get_config(name)
+    arch = dict(cfg["arch"], n_layers=layers)
+    w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16")
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S,
+                                          n_image=min(cfg["n_image"], 200))
+    worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)
+    print(name, layers, "worst logits error abs/rel:", worst)
+
+
+def test_error_paths_on_device(oracle):
+    import paper_2512_07503_amd as sjd
+    from helpers import gpu_weights
+    cfg = workload.get_config("small_f32")
+    w = workload.make_weights(cfg["arch"], 1, 4.0)
+    g = sjd.Decoder(cfg["arch"], gpu_weights(w, "f32"), "f32", 4, 32, max_seqs=2, top_k=10)
+    with pytest.raises(sjd.SjdError) as e:
+        g.n_seqs = 1
+        g.step()
+    assert e.value.code == -3                                     # step before prefill
+    cond, uncond = workload.make_prompts(cfg["arch"], 1, 3, 6)
+    assert g.prefill(cond, uncond, [5, 5, 5]) == -5               # more sequences than max_seqs
+    assert g.prefill(cond[:1], uncond[:1], [40]) == -5            # prompt + image > max_ctx
+    bad = [np.array([1, 2, cfg["arch"]["vocab"]], dtype=np.int32)]
+    assert g.prefill(bad, uncond[:1], [5]) == -1                  # id outside the vocabulary
+    assert g.prefill(cond[:2], uncond[:2], [5, 7]) == 0
+    hist = g.decode(100)
+    assert all(x["done"] for x in hist[-1])
+    again = g.step()                                              # stepping a finished decode is a no-op
+    assert all(x["done"] == 1 and x["n_finalized"] == 0 for x in again)
+    assert len(g.tokens(0)) == 5 and len(g.tokens(1)) == 7
+    assert g.prefill(cond[:1], uncond[:1], [3]) == 0              # a context can be reused
+    g.decode(100)
+    assert len(g.tokens(0)) == 3
