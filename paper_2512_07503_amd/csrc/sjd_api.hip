@@ -552,6 +552,7 @@ int sjd_prefill(sjd_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, cons
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->prompt_last_dev, plast.data(), plast.size() * 4, hipMemcpyHostToDevice, st));
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->n_image_dev, n_image_tokens, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->page_table, table.data(), table.size() * 4, hipMemcpyHostToDevice, st));
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(st));  // the host staging vectors may go away on an early return
     const int chunks = ceil_div(max_prompt - 1, L);
     for (int ch = 0; ch < chunks; ++ch) {
         SJD_LAUNCH(c, KC_STAGE, launch_stage_prompt(st, c->rm, c->prompt_dev, c->prompt_len_dev, max_prompt, ch, L, n_seqs));
