@@ -167,7 +167,7 @@ def main():
     mean_ctx = mean_ctx_sum / max(traced, 1)
     kernels = {}
     for name, (launches, total_ms) in tr.items():
-        if launches == 0:
+        if launches == 0 or traced == 0:
             continue
         avg_ms = total_ms / launches
         entry = {"launches_per_step": launches / traced, "avg_us": round(1e3 * avg_ms, 2),
@@ -179,15 +179,15 @@ def main():
             m, n, k = gemm_shapes(arch, M)[name]
             entry["TFLOPs"] = round(2.0 * m * n * k / (avg_ms * 1e-3) / 1e12, 2)
         kernels[name] = entry
-    dominant = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    dom = kernels[dominant]
-    roofline = {"kernel": dominant, "bound": "hbm", "achieved": dom.get("GBps"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    roofline = None
+    dominant = max(kernels, key=lambda n: kernels[n]["ms_per_step"]) if kernels else None
+    dom = kernels.get(dominant)
+    if dom: roofline = {"kernel": dominant, "bound": "hbm", "achieved": dom.get("GBps"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4) if dom.get("GBps") else None, "traffic": None,
                 "avg_us": dom["avg_us"], "launches_per_step": dom["launches_per_step"]}
-    if dominant.startswith("gemm") and M >= 320:      # above the ridge (~312 flop/B) the contraction is MFMA-bound
+    if dom and dominant.startswith("gemm") and M >= 320:      # above the ridge (~312 flop/B) the contraction is MFMA-bound
         roofline.update({"bound": "mfma", "achieved": dom["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(dom["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)})
-    weight_bytes = sum(n * k for (_, n, k) in gemm_shapes(arch, M).values() if True) * 0
     esz = 4 if cfg["dtype"] == "f32" else 2
     shp = gemm_shapes(arch, M)
     step_weight_bytes = esz * (arch["n_layers"] * sum(shp[g][1] * shp[g][2] for g in ("gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down"))
