@@ -94,3 +94,187 @@ __global__ void pack_q_kernel(const T *__restrict__ src, T *__restrict__ dst, in
         dst[(size_t)h * Layout<T>::q_elems(L, hd) + Layout<T>::q_index(i, j, hd)] = src[idx];
     }
 }
+
+// ------------------------------------------------------------------------------------ MFMA, bf16
+// Flash-decoding over the paged cache.  A wavefront owns one (segment, query head, chunk of `chunk`
+// tokens) and all L <= 32 queries of the window.  Per block of 32 tokens:
+//   S^T (tokens x queries) = K (A operand, fragment-major page) x Q^T (B operand)       hd / 16 MFMAs
+//   online softmax per query = per accumulator column: in-lane over 16 values + one cross-half shuffle
+//   O^T (dims x queries)  += V^T (A operand) x P^T (B operand)                            2 hd / 32 MFMAs
+// P^T needs no data movement: accumulator registers 8 i .. 8 i + 7 of S^T, rounded to bf16, ARE the B
+// operand of the i-th PV MFMA, because the value pages are stored in the matching token order
+// (Layout<bf16_t>::v_index).  Keys and values stream from HBM exactly once per (segment, kv head):
+// the G query heads of a kv head run as G wavefronts of one workgroup and share the fetches in L1/L2.
+// Chunks are merged by attention_combine_kernel.
+struct AttnArgs {
+    const bf16_t *q;       // [segments][H][q_elems(L, hd)]
+    KvPool pool;
+    const int32_t *row_tok;  // [segments * L]
+    const int32_t *seg_kv;   // cached positions per segment
+    const int32_t *seg_n;    // active window rows per segment
+    float *part_o;           // [segments * H * n_chunks][32][hd]
+    float *part_ml;          // [segments * H * n_chunks][2][32]  (running max, running sum)
+    bf16_t *out_act;         // [M][H * hd] GEMM-operand layout
+    float *out_plain;        // optional [M][H][hd]
+    int L, H, Hkv, hd, chunk, n_chunks;
+    float scale_log2e;       // 1 / sqrt(hd) * log2(e)
+};
+
+template <int HD>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
+    constexpr int KF = HD / 16, DB = HD / 32;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int G = a.H / a.Hkv;
+    const int c = blockIdx.x, kvh = blockIdx.y, seg = blockIdx.z;
+    const int h = kvh * G + wave;
+    const int n_act = a.seg_n[seg];
+    const int kv = a.seg_kv[seg];
+    const int n_tot = n_act > 0 ? kv + n_act : 0;
+    const int t_begin = c * a.chunk;
+    if (t_begin >= n_tot) return;
+    const int t_end = t_begin + a.chunk < n_tot ? t_begin + a.chunk : n_tot;
+
+    const u32x4 *qp = reinterpret_cast<const u32x4 *>(a.q + ((size_t)seg * a.H + h) * Layout<bf16_t>::q_elems(a.L, HD)) + lane;
+    u32x4 qf[KF];
+#pragma unroll
+    for (int kb = 0; kb < KF; ++kb) qf[kb] = qp[kb * 64];
+
+    const int32_t *pt = a.pool.page_table + (size_t)seg * a.pool.pages_per_seg;
+    const int ptok = a.pool.page_tokens;
+    const size_t blk = (size_t)ptok * HD;  // elements of one (page, kv head) block
+    auto kfrag = [&](int t0) {            // first fragment of the 32-token block starting at t0
+        return reinterpret_cast<const u32x4 *>((const bf16_t *)a.pool.k + ((size_t)pt[t0 / ptok] * a.Hkv + kvh) * blk) +
+               (size_t)((t0 % ptok) >> 5) * KF * 64 + lane;
+    };
+    auto vfrag = [&](int t0) {
+        return reinterpret_cast<const u32x4 *>((const bf16_t *)a.pool.v + ((size_t)pt[t0 / ptok] * a.Hkv + kvh) * blk) +
+               (size_t)((t0 % ptok) >> 5) * 2 * DB * 64 + lane;
+    };
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;  // per query (= lane % 32); l_run is this lane's half only
+    const int query = lane & 31;
+
+    u32x4 kf[KF], vf[2 * DB];
+    {
+        const u32x4 *kp = kfrag(t_begin);
+#pragma unroll
+        for (int kb = 0; kb < KF; ++kb) kf[kb] = kp[kb * 64];
+        const u32x4 *vp = vfrag(t_begin);
+#pragma unroll
+        for (int f = 0; f < 2 * DB; ++f) vf[f] = vp[f * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < KF; ++kb)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kb]), __builtin_bit_cast(bf16x8, qf[kb]), s, 0, 0, 0);
+        // next block's keys while this block's softmax and PV run (clamped to the last block: a cache hit)
+        const int tn = t0 + 32 < t_end ? t0 + 32 : t0;
+        {
+            const u32x4 *kp = kfrag(tn);
+#pragma unroll
+            for (int kb = 0; kb < KF; ++kb) kf[kb] = kp[kb * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // scores -> base-2 logits, causal / length mask
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tok = t0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const bool vis = tok <= kv + query && tok < n_tot;
+            s[v] = vis ? s[v] * a.scale_log2e : -INFINITY;
+            mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        // a query with nothing visible so far keeps m = -inf; avoid (-inf) - (-inf)
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        const float alpha = exp2f(m_run - m_use);
+        float psum = 0.0f;
+        uint32_t pk[8];
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+            const float p0 = exp2f(s[v] - m_use), p1 = exp2f(s[v + 1] - m_use);
+            const bf16_t b0 = float_to_bf16(p0), b1 = float_to_bf16(p1);
+            psum += bf16_to_float(b0) + bf16_to_float(b1);  // the sum of what is actually multiplied
+            pk[v >> 1] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        const u32x4 p0 = {pk[0], pk[1], pk[2], pk[3]}, p1 = {pk[4], pk[5], pk[6], pk[7]};
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[db]), __builtin_bit_cast(bf16x8, p0), o[db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[DB + db]), __builtin_bit_cast(bf16x8, p1), o[db], 0, 0, 0);
+        }
+        {
+            const u32x4 *vp = vfrag(tn);
+#pragma unroll
+            for (int f = 0; f < 2 * DB; ++f) vf[f] = vp[f * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run += __shfl_xor(l_run, 32, 64);
+    const size_t slot = ((size_t)seg * a.H + h) * a.n_chunks + c;
+    float *po = a.part_o + slot * 32 * HD + (size_t)query * HD;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) po[db * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = o[db][v];
+    if (lane < 32) {
+        a.part_ml[slot * 64 + query] = m_run;
+        a.part_ml[slot * 64 + 32 + query] = l_run;
+    }
+}
+
+// Merges the chunks of every (row, head): out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
+__global__ void attention_combine_kernel(AttnArgs a) {
+    const int m = blockIdx.x, h = blockIdx.y;
+    const int seg = m / a.L, i_win = m % a.L, hd = a.hd;
+    const bool active = a.row_tok[m] >= 0;
+    const int n_tot = a.seg_kv[seg] + a.seg_n[seg];
+    const int nc = active ? (n_tot + a.chunk - 1) / a.chunk : 0;
+    const size_t slot0 = ((size_t)seg * a.H + h) * a.n_chunks;
+    float mx = -INFINITY;
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, a.part_ml[(slot0 + c) * 64 + i_win]);
+    float denom = 0.0f;
+    for (int c = 0; c < nc; ++c) denom += exp2f(a.part_ml[(slot0 + c) * 64 + i_win] - mx) * a.part_ml[(slot0 + c) * 64 + 32 + i_win];
+    const float inv = nc > 0 ? 1.0f / denom : 0.0f;
+    for (int j = threadIdx.x; j < hd; j += blockDim.x) {
+        float acc = 0.0f;
+        for (int c = 0; c < nc; ++c)
+            acc += exp2f(a.part_ml[(slot0 + c) * 64 + i_win] - mx) * a.part_o[(slot0 + c) * 32 * hd + (size_t)i_win * hd + j];
+        acc *= inv;
+        if (a.out_act) a.out_act[Layout<bf16_t>::a_index(m, h * hd + j, a.H * hd)] = float_to_bf16(acc);
+        if (a.out_plain) a.out_plain[((size_t)m * a.H + h) * hd + j] = acc;
+    }
+}
+
+inline bool attention_mfma_supported(int L, int H, int Hkv, int hd, int page_tokens) {
+    return L <= 32 && (hd == 64 || hd == 128) && H / Hkv <= 4 && page_tokens % 32 == 0;
+}
+
+// n_segments segments of L rows each; max_tokens bounds cache + window of any segment
+inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n_segments) {
+    dim3 grid(a.n_chunks, a.Hkv, n_segments);
+    const int G = a.H / a.Hkv;
+    if (a.hd == 64) attention_mfma_kernel<64><<<grid, G * 64, 0, st>>>(a);
+    else attention_mfma_kernel<128><<<grid, G * 64, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    attention_combine_kernel<<<dim3(n_segments * a.L, a.H), a.hd <= 64 ? 64 : 128, 0, st>>>(a);
+    return hipGetLastError();
+}

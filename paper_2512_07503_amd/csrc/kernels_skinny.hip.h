@@ -1,0 +1,281 @@
+// Fused projection kernels for small row counts (M = 2 * sequences * window <= 64): the regime of
+// Sec. 4.1 Step 2 where every GEMM of the forward is bound by streaming its weights from HBM once.
+//
+// One workgroup of NW wavefronts owns NBW column blocks of 32 and ALL of K: wavefront w takes the
+// k-blocks w, w + NW, w + 2 NW, ... and keeps a ring of DEPTH fragment loads in flight (each a fully
+// coalesced 1 KiB read of fragment-major W straight into MFMA operand registers); the NW partial
+// accumulators are summed through LDS, so no partial sums ever go to HBM and the epilogue sees final
+// values.  The epilogues absorb what would otherwise be separate memory-bound kernels:
+//   QKV     per-row RMSNorm scale, rotary embedding, queries to the attention layout, keys/values into
+//           their KV pages
+//   RESID   residual add into the fp32 stream + the bf16 copy of the stream that feeds the next GEMM
+//   SWIGLU  per-row RMSNorm scale, silu(gate) * up
+//   HEAD    per-row RMSNorm scale, fp32 logits
+// RMSNorm is folded in: the gain is multiplied into the weights when they are packed, the input is
+// the raw residual stream in bf16, its per-row sum of squares is accumulated from the very A fragments
+// the MFMA consumes, and the row scale 1/rms is applied to the accumulators (it commutes with the
+// contraction).
+#pragma once
+#include "common.hip.h"
+#include "kernels_forward.hip.h"
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+
+struct SkinnyArgs {
+    const bf16_t *A;   // [MT][KB][64][8] raw activations, fragment-major
+    const bf16_t *W;   // [groups * NBW][KB][64][8]
+    int M, KB;
+    float eps;
+    // RESID
+    float *x;          // [M][N] fp32 residual stream, updated in place
+    bf16_t *xb;        // the same in bf16, fragment-major [M][N]
+    int N;             // also the logits row length for HEAD
+    // QKV
+    const int32_t *row_tok, *row_pos;
+    const float *rope_cos, *rope_sin;
+    bf16_t *q_out;
+    KvPool pool;
+    int L, H, Hkv, hd;
+    // SWIGLU
+    bf16_t *h;
+    int F;
+    // HEAD
+    float *logits;
+};
+
+template <int MT, int NBW, int NW, int DEPTH, int EPI>
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
+    constexpr bool kNorm = EPI != EPI_RESID;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
+    const int g = blockIdx.x, KB = a.KB;
+    const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
+    const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + lane;
+    const int n_it = wave < KB ? (KB - wave + NW - 1) / NW : 0;
+
+    f32x16 acc[MT][NBW];
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int i = 0; i < NBW; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
+    float ssq[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) ssq[j] = 0.0f;
+
+    // Ring of DEPTH slots.  The loop body is branch-free so that the compiler can count outstanding loads
+    // exactly (a slot is consumed while the DEPTH - 1 younger ones are still in flight): iterations past the
+    // end re-read the last fragment (a cache hit) and contribute nothing because their A operand is zeroed.
+    if (n_it > 0) {
+        u32x4 bq[DEPTH][NBW], aq[DEPTH][MT];
+        const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            const size_t kb = (size_t)(wave + (s < n_it ? s : n_it - 1) * NW);
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
+#pragma unroll
+            for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        for (int it0 = 0; it0 < n_it; it0 += DEPTH) {
+#pragma unroll
+            for (int s = 0; s < DEPTH; ++s) {
+                const int it = it0 + s;
+                const bool valid = it < n_it;
+#pragma unroll
+                for (int j = 0; j < MT; ++j) {
+                    const u32x4 araw = valid ? aq[s][j] : zero4;
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, araw);
+                    if (kNorm) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t pr = araw[e];
+                            const float lo = __builtin_bit_cast(float, pr << 16), hi = __builtin_bit_cast(float, pr & 0xFFFF0000u);
+                            ssq[j] = fmaf(lo, lo, ssq[j]);
+                            ssq[j] = fmaf(hi, hi, ssq[j]);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < NBW; ++i)
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq[s][i]), acc[j][i], 0, 0, 0);
+                }
+                const int nx = it + DEPTH;
+                const size_t kb = (size_t)(wave + (nx < n_it ? nx : n_it - 1) * NW);
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
+#pragma unroll
+                for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+                __builtin_amdgcn_sched_barrier(0);  // keep the refill here: the scheduler must not sink it towards its use
+            }
+        }
+    }
+
+    // ---- sum the NW partial tiles through LDS; thread t ends up with elements e = t and t + 512 of every
+    //      tile: accumulator register v = e / 64 of lane l = e % 64, i.e. row 8 (v / 4) + 4 (l / 32) + v % 4,
+    //      column l % 32.
+    __shared__ float red[NW][16][64];
+    __shared__ float ssq_lds[NW][MT][32];
+    if (kNorm) {
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            const float t = ssq[j] + __shfl_xor(ssq[j], 32, 64);
+            if (lane < 32) ssq_lds[wave][j][lane] = t;
+        }
+    }
+    constexpr int EPT = 1024 / (NW * 64);  // elements per thread per tile
+    float out[MT][NBW][EPT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[j][i][v];
+            __syncthreads();
+#pragma unroll
+            for (int hh = 0; hh < EPT; ++hh) {
+                const int v = wave + NW * hh;
+                float s = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) s += red[w][v][lane];
+                out[j][i][hh] = s;
+            }
+        }
+
+    const int col = lane & 31;
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int hh = 0; hh < EPT; ++hh) {
+            const int v = wave + NW * hh;
+            const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const int m = j * 32 + row;
+            if (m >= a.M) continue;
+            float inv = 1.0f;
+            if (kNorm) {
+                float t = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) t += ssq_lds[w][j][row];
+                inv = 1.0f / sqrtf(t / (float)(KB * 16) + a.eps);
+            }
+            if (EPI == EPI_RESID) {
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int n = (g * NBW + i) * 32 + col;
+                    if (n < a.N) {
+                        const float nv = a.x[(size_t)m * a.N + n] + out[j][i][hh];
+                        a.x[(size_t)m * a.N + n] = nv;
+                        a.xb[Layout<bf16_t>::a_index(m, n, a.N)] = float_to_bf16(nv);
+                    }
+                }
+            } else if (EPI == EPI_HEAD) {
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int n = (g * NBW + i) * 32 + col;
+                    if (n < a.N) a.logits[(size_t)m * a.N + n] = out[j][i][hh] * inv;
+                }
+            } else if (EPI == EPI_SWIGLU) {
+                // tile 0 = gate columns [32 g, 32 g + 32), tile 1 = the matching up columns
+                const float gt = out[j][0][hh] * inv, up = out[j][1][hh] * inv;
+                const int n = g * 32 + col;
+                if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
+            } else {  // EPI_QKV: group g = (head hh_, sub-block sub); tiles = dims j0 = 32 sub + col and j0 + hd / 2
+                if (a.row_tok[m] < 0) continue;
+                const int pairs = a.hd >> 6;
+                const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
+                const int j0 = sub * 32 + col, j1 = j0 + half;
+                const int seg = m / a.L, i_win = m % a.L, pos = a.row_pos[m];
+                float v0 = out[j][0][hh] * inv, v1 = out[j][1][hh] * inv;
+                if (head < a.H + a.Hkv) {
+                    const float c = a.rope_cos[(size_t)pos * half + j0], s = a.rope_sin[(size_t)pos * half + j0];
+                    const float r0 = v0 * c - v1 * s, r1 = v1 * c + v0 * s;
+                    v0 = r0;
+                    v1 = r1;
+                }
+                if (head < a.H) {
+                    bf16_t *dst = a.q_out + ((size_t)seg * a.H + head) * Layout<bf16_t>::q_elems(a.L, a.hd);
+                    dst[Layout<bf16_t>::q_index(i_win, j0, a.hd)] = float_to_bf16(v0);
+                    dst[Layout<bf16_t>::q_index(i_win, j1, a.hd)] = float_to_bf16(v1);
+                } else {
+                    const int page = a.pool.page_table[seg * a.pool.pages_per_seg + pos / a.pool.page_tokens];
+                    const int t = pos % a.pool.page_tokens;
+                    const size_t blk = (size_t)a.pool.page_tokens * a.hd;
+                    if (head < a.H + a.Hkv) {
+                        bf16_t *dst = (bf16_t *)a.pool.k + ((size_t)page * a.Hkv + (head - a.H)) * blk;
+                        dst[Layout<bf16_t>::k_index(t, j0, a.hd)] = float_to_bf16(v0);
+                        dst[Layout<bf16_t>::k_index(t, j1, a.hd)] = float_to_bf16(v1);
+                    } else {
+                        bf16_t *dst = (bf16_t *)a.pool.v + ((size_t)page * a.Hkv + (head - a.H - a.Hkv)) * blk;
+                        dst[Layout<bf16_t>::v_index(t, j0, a.hd)] = float_to_bf16(v0);
+                        dst[Layout<bf16_t>::v_index(t, j1, a.hd)] = float_to_bf16(v1);
+                    }
+                }
+            }
+        }
+}
+
+// Embedding gather for the fused path: fp32 residual stream + its bf16 fragment-major copy.
+__global__ void embed_dual_kernel(const bf16_t *__restrict__ emb, const int32_t *__restrict__ row_tok, float *__restrict__ x,
+                                  bf16_t *__restrict__ xb, int d) {
+    const int m = blockIdx.x;
+    const int tok = row_tok[m];
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        const bf16_t v = tok >= 0 ? emb[(size_t)tok * d + i] : (bf16_t)0;
+        x[(size_t)m * d + i] = bf16_to_float(v);
+        xb[Layout<bf16_t>::a_index(m, i, d)] = v;
+    }
+}
+
+// Weight re-layout for the fused path.  dst block (group * nbw + i) of 32 rows <- source rows given by
+// `map`: src_row = map(dst_row); gain (may be NULL) is multiplied into column k.
+struct PackMap {
+    int mode;     // 0 identity, 1 = QKV head/pair order, 2 = gate/up interleave
+    int hd, F;    // mode 1: head dimension; mode 2: rows of the gate matrix
+};
+SJD_HD int packmap_src_row(const PackMap &pm, int dst_row) {
+    if (pm.mode == 1) {  // groups of 64 rows: head = grp / pairs, sub = grp % pairs; tile i -> block sub + i * pairs
+        const int pairs = pm.hd >> 6, grp = dst_row >> 6, i = (dst_row >> 5) & 1, c = dst_row & 31;
+        const int head = grp / pairs, sub = grp % pairs;
+        return head * pm.hd + (sub + i * pairs) * 32 + c;
+    }
+    if (pm.mode == 2) {  // groups of 64 rows: 32 gate rows then the 32 up rows of the same columns
+        const int grp = dst_row >> 6, i = (dst_row >> 5) & 1, c = dst_row & 31;
+        return i * pm.F + grp * 32 + c;
+    }
+    return dst_row;
+}
+
+// src: logical [N][K] matrix given as up to 3 row-major pieces stacked by rows (n0, n1 = end rows of piece 0, 1)
+__global__ void pack_weight_fused_kernel(const bf16_t *__restrict__ s0, const bf16_t *__restrict__ s1, const bf16_t *__restrict__ s2,
+                                         int n0, int n1, const float *__restrict__ gain, bf16_t *__restrict__ dst, int N, int K,
+                                         PackMap pm) {
+    const size_t total = (size_t)N * K;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int nd = (int)(idx / K), k = (int)(idx % K);
+        const int ns = packmap_src_row(pm, nd);
+        if (ns >= N) continue;  // rows beyond the matrix stay zero
+        const bf16_t *src = ns < n0 ? s0 + (size_t)ns * K : (ns < n1 ? s1 + (size_t)(ns - n0) * K : s2 + (size_t)(ns - n1) * K);
+        float v = bf16_to_float(src[k]);
+        if (gain) v *= gain[k];
+        dst[Layout<bf16_t>::w_index(nd, k, K)] = float_to_bf16(v);
+    }
+}
+
+template <int EPI>
+inline hipError_t launch_skinny(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw) {
+    constexpr int NW = 8, DEPTH = 8;
+    if (nbw == 2) {
+        if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<groups, NW * 64, 0, st>>>(a);
+        else gemm_skinny_kernel<2, 2, NW, DEPTH, EPI><<<groups, NW * 64, 0, st>>>(a);
+    } else {
+        if (EPI == EPI_RESID || EPI == EPI_HEAD) {
+            if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, EPI == EPI_HEAD ? EPI_HEAD : EPI_RESID><<<groups, NW * 64, 0, st>>>(a);
+            else gemm_skinny_kernel<2, 1, NW, DEPTH, EPI == EPI_HEAD ? EPI_HEAD : EPI_RESID><<<groups, NW * 64, 0, st>>>(a);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    return hipGetLastError();
+}

@@ -14,6 +14,7 @@
 #include "kernels_attention.hip.h"
 #include "kernels_forward.hip.h"
 #include "kernels_gemm.hip.h"
+#include "kernels_skinny.hip.h"
 
 void sjd_set_error(char *buf, const char *fmt, ...) {
     if (!buf) return;
@@ -60,6 +61,10 @@ struct sjd_ctx {
     int hd = 0, Vs = 0, L = 0, S = 0, n_seqs = 0, pt = 0, pps = 0, n_pages = 0, max_visible = 0;
     size_t esize = 0;
     bool prefilled = false, all_done = false;
+    bool attn_mfma = false;
+    int attn_chunk = 0, attn_nchunks = 0;
+    float *part_o = nullptr, *part_ml = nullptr;
+    bool fused = false;  // small-M path: fused projection kernels, RMSNorm gains folded into the weights
     // weights (owned)
     void *tok_emb = nullptr, *lm_head = nullptr;
     float *final_norm = nullptr;
@@ -184,6 +189,41 @@ int run_gemm<bf16_t>(sjd_ctx *c, int cls, const bf16_t *A, const bf16_t *W, floa
     return SJD_OK;
 }
 
+// ---------------------------------------------------------------------------------------- attention
+template <typename T> int run_attention(sjd_ctx *c, const KvPool &pool, int M);
+
+template <> int run_attention<float>(sjd_ctx *c, const KvPool &pool, int M) {
+    SJD_LAUNCH(c, KC_ATTENTION, launch_attention_reference<float>(c->stream, (const float *)c->q, pool, c->rm.row_tok, c->rm.seg_kv,
+                                                                  (float *)c->attn, nullptr, M, c->L, c->md.n_heads,
+                                                                  c->md.n_kv_heads, c->hd, c->max_visible));
+    return SJD_OK;
+}
+
+template <> int run_attention<bf16_t>(sjd_ctx *c, const KvPool &pool, int M) {
+    if (!c->attn_mfma) {
+        SJD_LAUNCH(c, KC_ATTENTION, launch_attention_reference<bf16_t>(c->stream, (const bf16_t *)c->q, pool, c->rm.row_tok,
+                                                                       c->rm.seg_kv, (bf16_t *)c->attn, nullptr, M, c->L,
+                                                                       c->md.n_heads, c->md.n_kv_heads, c->hd, c->max_visible));
+        return SJD_OK;
+    }
+    AttnArgs a;
+    a.q = (const bf16_t *)c->q;
+    a.pool = pool;
+    a.row_tok = c->rm.row_tok;
+    a.seg_kv = c->rm.seg_kv;
+    a.seg_n = c->rm.seg_n;
+    a.part_o = c->part_o;
+    a.part_ml = c->part_ml;
+    a.out_act = (bf16_t *)c->attn;
+    a.out_plain = nullptr;
+    a.L = c->L; a.H = c->md.n_heads; a.Hkv = c->md.n_kv_heads; a.hd = c->hd;
+    a.chunk = c->attn_chunk;
+    a.n_chunks = c->attn_nchunks;
+    a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)c->hd));
+    SJD_LAUNCH(c, KC_ATTENTION, launch_attention_mfma(c->stream, a, M / c->L));
+    return SJD_OK;
+}
+
 // ------------------------------------------------------------------------------------------ forward
 // Runs the rows described by c->rm through the model.  Keys and values of active rows are written to
 // their pages; with_head also produces fp32 logits [M][V_s].
@@ -214,8 +254,7 @@ template <typename T> int forward(sjd_ctx *c, bool with_head) {
                        rope_kv_kernel<T><<<M, 256, 0, st>>>(c->partial, splits, M, c->rm.row_tok, c->rm.row_pos, c->rope_cos,
                                                             c->rope_sin, (T *)c->q, pool, c->L, H, Hkv, hd);
                    }));
-        SJD_LAUNCH(c, KC_ATTENTION, launch_attention_reference<T>(st, (const T *)c->q, pool, c->rm.row_tok, c->rm.seg_kv,
-                                                                  (T *)c->attn, nullptr, M, c->L, H, Hkv, hd, c->max_visible));
+        if ((rc = run_attention<T>(c, pool, M))) return rc;
         rc = run_gemm<T>(c, KC_GEMM_O, (const T *)c->attn, (const T *)lw.wo, c->partial, M, d, H * hd, 0, &splits);
         if (rc) return rc;
         SJD_LAUNCH(c, KC_ADDNORM, after([&] {
@@ -239,7 +278,59 @@ template <typename T> int forward(sjd_ctx *c, bool with_head) {
     return SJD_OK;
 }
 
+// Small-M bf16 path: five kernels per layer (QKV+RoPE+KV write, attention, out+residual, gate/up+SwiGLU,
+// down+residual); c->xn holds the bf16 copy of the residual stream.
+int forward_fused(sjd_ctx *c, bool with_head) {
+    const sjd_model_desc &md = c->md;
+    const int M = c->n_seqs * 2 * c->L, d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
+    const int MT = ceil_div(M, 32);
+    hipStream_t st = c->stream;
+    SJD_LAUNCH(c, KC_EMBED, after([&] {
+                   embed_dual_kernel<<<M, 256, 0, st>>>((const bf16_t *)c->tok_emb, c->rm.row_tok, c->x, (bf16_t *)c->xn, d);
+               }));
+    SkinnyArgs a;
+    memset(&a, 0, sizeof a);
+    a.M = M;
+    a.eps = md.rms_eps;
+    a.row_tok = c->rm.row_tok;
+    a.row_pos = c->rm.row_pos;
+    a.rope_cos = c->rope_cos;
+    a.rope_sin = c->rope_sin;
+    a.q_out = (bf16_t *)c->q;
+    a.L = c->L; a.H = H; a.Hkv = Hkv; a.hd = hd; a.F = F;
+    a.x = c->x;
+    a.xb = (bf16_t *)c->xn;
+    a.h = (bf16_t *)c->h;
+    a.logits = c->logits;
+    const int nbw_d = ceil_div(d, 32) >= 128 ? 2 : 1;
+    for (int l = 0; l < md.n_layers; ++l) {
+        const LayerWeights &lw = c->layers[l];
+        KvPool pool;
+        pool.k = (char *)c->kpool + c->pool_layer_bytes * l;
+        pool.v = (char *)c->vpool + c->pool_layer_bytes * l;
+        pool.page_table = c->page_table;
+        pool.pages_per_seg = c->pps;
+        pool.page_tokens = c->pt;
+        a.pool = pool;
+        a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wqkv; a.KB = d / 16;
+        SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2));
+        { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
+        a.A = (const bf16_t *)c->attn; a.W = (const bf16_t *)lw.wo; a.KB = H * hd / 16; a.N = d;
+        SJD_LAUNCH(c, KC_GEMM_O, launch_skinny<EPI_RESID>(st, a, MT, ceil_div(ceil_div(d, 32), nbw_d), nbw_d));
+        a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
+        SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2));
+        a.A = (const bf16_t *)c->h; a.W = (const bf16_t *)lw.wdown; a.KB = F / 16; a.N = d;
+        SJD_LAUNCH(c, KC_GEMM_DOWN, launch_skinny<EPI_RESID>(st, a, MT, ceil_div(ceil_div(d, 32), nbw_d), nbw_d));
+    }
+    if (with_head) {
+        a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
+        SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2));
+    }
+    return SJD_OK;
+}
+
 int forward_any(sjd_ctx *c, bool with_head) {
+    if (c->fused) return forward_fused(c, with_head);
     return c->md.dtype == SJD_F32 ? forward<float>(c, with_head) : forward<bf16_t>(c, with_head);
 }
 
@@ -293,6 +384,53 @@ template <typename T> int copy_weights(sjd_ctx *c, const sjd_weights *w) {
     return SJD_OK;
 }
 
+// Weights of the fused small-M path: gains folded in, QKV rows in (head, rotary pair) order, gate and up
+// interleaved by blocks of 32.
+int copy_weights_fused(sjd_ctx *c, const sjd_weights *w) {
+    typedef bf16_t T;
+    const sjd_model_desc &md = c->md;
+    const int d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
+    hipStream_t st = c->stream;
+    int rc;
+    T *emb;
+    if ((rc = dev_alloc(c, &emb, (size_t)md.vocab * d * sizeof(T), false))) return rc;
+    SJD_HIP_TRY(c->err, hipMemcpyAsync(emb, w->tok_emb, (size_t)md.vocab * d * sizeof(T), hipMemcpyDeviceToDevice, st));
+    c->tok_emb = emb;
+    float *gain;  // scratch, reused per matrix (stream order keeps it safe)
+    if ((rc = dev_alloc(c, &gain, (size_t)d * sizeof(float)))) return rc;
+    auto pack = [&](T *dst, const void *s0, const void *s1, const void *s2, int n0, int n1, int N, int K, const void *g,
+                    PackMap pm) -> int {
+        if (!s0 || (n0 < N && !s1) || (n1 < N && !s2)) { sjd_set_error(c->err, "null weight pointer"); return SJD_EINVAL; }
+        if (g) to_float_kernel<T><<<ceil_div(K, 256), 256, 0, st>>>((const T *)g, gain, K);
+        pack_weight_fused_kernel<<<2048, 256, 0, st>>>((const T *)s0, (const T *)s1, (const T *)s2, n0, n1, g ? gain : nullptr, dst,
+                                                       N, K, pm);
+        return hipGetLastError() == hipSuccess ? SJD_OK : SJD_EDEVICE;
+    };
+    const PackMap ident{0, hd, F}, qkvmap{1, hd, F}, gumap{2, hd, F};
+    T *head;
+    if ((rc = dev_alloc(c, &head, Layout<T>::w_elems(ceil_div(c->Vs, 64) * 64, d) * sizeof(T)))) return rc;
+    if ((rc = pack(head, (const T *)w->lm_head + (size_t)md.sample_lo * d, nullptr, nullptr, c->Vs, c->Vs, c->Vs, d, w->final_norm, ident)))
+        return rc;
+    c->lm_head = head;
+    c->layers.resize(md.n_layers);
+    const int Nqkv = (H + 2 * Hkv) * hd, dpad = ceil_div(d, 64) * 64;
+    for (int l = 0; l < md.n_layers; ++l) {
+        LayerWeights &lw = c->layers[l];
+        if (!w->attn_norm[l] || !w->mlp_norm[l]) { sjd_set_error(c->err, "null weight pointer"); return SJD_EINVAL; }
+        T *qkv, *o, *gu, *down;
+        if ((rc = dev_alloc(c, &qkv, Layout<T>::w_elems(Nqkv, d) * sizeof(T)))) return rc;
+        if ((rc = pack(qkv, w->wq[l], w->wk[l], w->wv[l], H * hd, (H + Hkv) * hd, Nqkv, d, w->attn_norm[l], qkvmap))) return rc;
+        if ((rc = dev_alloc(c, &o, Layout<T>::w_elems(dpad, H * hd) * sizeof(T)))) return rc;
+        if ((rc = pack(o, w->wo[l], nullptr, nullptr, d, d, d, H * hd, nullptr, ident))) return rc;
+        if ((rc = dev_alloc(c, &gu, Layout<T>::w_elems(2 * F, d) * sizeof(T)))) return rc;
+        if ((rc = pack(gu, w->w_gate[l], w->w_up[l], nullptr, F, 2 * F, 2 * F, d, w->mlp_norm[l], gumap))) return rc;
+        if ((rc = dev_alloc(c, &down, Layout<T>::w_elems(dpad, F) * sizeof(T)))) return rc;
+        if ((rc = pack(down, w->w_down[l], nullptr, nullptr, d, d, d, F, nullptr, ident))) return rc;
+        lw.wqkv = qkv; lw.wo = o; lw.wgu = gu; lw.wdown = down;
+    }
+    return SJD_OK;
+}
+
 template <typename T> int alloc_buffers(sjd_ctx *c) {
     const sjd_model_desc &md = c->md;
     const int S = c->S, L = c->L, M = S * 2 * L, d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
@@ -328,6 +466,17 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &c->attn, Layout<T>::a_elems(M, H * hd) * sizeof(T)))) return rc;
     if ((rc = dev_alloc(c, &c->h, Layout<T>::a_elems(M, F) * sizeof(T)))) return rc;
     if ((rc = dev_alloc(c, &c->q, (size_t)S * 2 * H * Layout<T>::q_elems(L, hd) * sizeof(T)))) return rc;
+    if (c->attn_mfma) {
+        // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
+        long want = (long)md.max_ctx * S * 2 * H / 1500;
+        int chunk = (int)((want + 63) / 64) * 64;
+        if (chunk < 128) chunk = 128;
+        c->attn_chunk = chunk;
+        c->attn_nchunks = ceil_div(md.max_ctx, chunk);
+        const size_t slots = (size_t)S * 2 * H * c->attn_nchunks;
+        if ((rc = dev_alloc(c, &c->part_o, slots * 32 * hd * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &c->part_ml, slots * 64 * sizeof(float)))) return rc;
+    }
     return SJD_OK;
 }
 
@@ -474,7 +623,11 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
     c->sp.top_k = sampling->top_k;
     c->sp.seed = sampling->seed;
     const bool f32 = desc->dtype == SJD_F32;
-    rc = f32 ? copy_weights<float>(c, weights) : copy_weights<bf16_t>(c, weights);
+    c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&
+                   attention_mfma_supported(c->L, desc->n_heads, desc->n_kv_heads, c->hd, c->pt);
+    c->fused = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) && c->hd % 64 == 0 && c->S * 2 * c->L <= 64 &&
+               desc->d_model % 32 == 0 && desc->d_ff % 32 == 0;
+    rc = f32 ? copy_weights<float>(c, weights) : (c->fused ? copy_weights_fused(c, weights) : copy_weights<bf16_t>(c, weights));
     if (!rc) rc = f32 ? alloc_buffers<float>(c) : alloc_buffers<bf16_t>(c);
     if (!rc) rc = alloc_state(c);
     if (!rc) rc = make_rope_tables(c);

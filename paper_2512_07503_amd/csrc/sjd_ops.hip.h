@@ -70,7 +70,6 @@ int op_gemm(hipStream_t st, int flags, const void *A, const void *W, float *C, i
 template <typename T>
 int op_attention(hipStream_t st, int flags, const void *q, const void *k, const void *v, float *out, int n, int ctx, int H,
                  int Hkv, int hd, int pt, int repeat, float *avg_ms) {
-    (void)flags;
     Scratch s;
     const int n_tok = ctx + n, pages = ceil_div(n_tok, pt);
     KvPool pool;
@@ -95,9 +94,30 @@ int op_attention(hipStream_t st, int flags, const void *q, const void *k, const 
     OP_TRY(hipGetLastError());
     pack_q_kernel<T><<<64, 256, 0, st>>>((const T *)q, qp, n, H, hd, n);
     OP_TRY(hipGetLastError());
+    const bool mfma = std::is_same<T, bf16_t>::value && !(flags & SJD_KERNELS_REFERENCE) && attention_mfma_supported(n, H, Hkv, hd, pt);
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    if (mfma) {
+        int32_t *seg_n;
+        a.chunk = 128;
+        a.n_chunks = ceil_div(n_tok, a.chunk);
+        if (!s.alloc(&a.part_o, (size_t)H * a.n_chunks * 32 * hd * sizeof(float), st) ||
+            !s.alloc(&a.part_ml, (size_t)H * a.n_chunks * 64 * sizeof(float), st) || !s.alloc(&seg_n, 4, st)) {
+            sjd_set_error(g_create_error, "allocation failed");
+            return SJD_ENOMEM;
+        }
+        OP_TRY(hipMemcpyAsync(seg_n, &n, 4, hipMemcpyHostToDevice, st));
+        OP_TRY(hipStreamSynchronize(st));
+        a.q = (const bf16_t *)qp; a.pool = pool; a.row_tok = row_tok; a.seg_kv = seg_kv; a.seg_n = seg_n;
+        a.out_act = nullptr; a.out_plain = out;
+        a.L = n; a.H = H; a.Hkv = Hkv; a.hd = hd;
+        a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)hd));
+    }
     OP_TRY(hipEventRecord(s.ev0, st));
-    for (int r = 0; r < repeat; ++r)
-        OP_TRY(launch_attention_reference<T>(st, qp, pool, row_tok, seg_kv, (T *)nullptr, out, n, n, H, Hkv, hd, n_tok + 1));
+    for (int r = 0; r < repeat; ++r) {
+        if (mfma) OP_TRY(launch_attention_mfma(st, a, 1));
+        else OP_TRY(launch_attention_reference<T>(st, qp, pool, row_tok, seg_kv, (T *)nullptr, out, n, n, H, Hkv, hd, n_tok + 1));
+    }
     OP_TRY(hipEventRecord(s.ev1, st));
     OP_TRY(hipStreamSynchronize(st));
     if (avg_ms) {

@@ -46,6 +46,9 @@ TINY = {
     "toy": _cfg(_arch(1, 16, 2, 2, 32, 8), "f32", 3, 3, 3, 8, 11),
     "small_f32": _cfg(_arch(2, 64, 4, 2, 128, 512), "f32", 9, 40, 8, 50, 12),
     "small_bf16": _cfg(_arch(2, 128, 4, 2, 256, 1024), "bf16", 11, 48, 16, 100, 13),
+    # shapes that take the fused small-M bf16 path (head_dim 64 / 128, M = 32 / 64)
+    "small_fused64": _cfg(_arch(2, 256, 4, 2, 512, 2048), "bf16", 13, 60, 16, 100, 15),
+    "small_fused128": _cfg(_arch(3, 256, 2, 1, 352, 1500, 20, 1460), "bf16", 70, 90, 32, 200, 16),
     "small_sub": _cfg(_arch(2, 64, 2, 1, 96, 700, 100, 612), "f32", 7, 30, 5, 40, 14, n_seqs=3),
 }
 
