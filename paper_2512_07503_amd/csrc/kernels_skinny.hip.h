@@ -41,6 +41,9 @@ struct SkinnyArgs {
     int F;
     // HEAD
     float *logits;
+#ifdef SJD_PHASE_TIMING
+    unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
+#endif
 };
 
 template <int MT, int NBW, int NW, int DEPTH, int EPI>
@@ -52,6 +55,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
     const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + lane;
     const int n_it = wave < KB ? (KB - wave + NW - 1) / NW : 0;
+#ifdef SJD_PHASE_TIMING
+#define SJD_STAMP(i) do { if (a.phase && tid == 0) a.phase[g * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SJD_STAMP(i) do { } while (0)
+#endif
+    SJD_STAMP(0);
 
     f32x16 acc[MT][NBW];
 #pragma unroll
@@ -112,6 +121,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         }
     }
 
+    SJD_STAMP(1);
     // ---- sum the NW partial tiles through LDS; thread t ends up with elements e = t and t + 512 of every
     //      tile: accumulator register v = e / 64 of lane l = e % 64, i.e. row 8 (v / 4) + 4 (l / 32) + v % 4,
     //      column l % 32.
@@ -144,6 +154,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             }
         }
 
+    SJD_STAMP(2);
     const int col = lane & 31;
 #pragma unroll
     for (int j = 0; j < MT; ++j)
@@ -214,6 +225,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 }
             }
         }
+    SJD_STAMP(3);
 }
 
 // Embedding gather for the fused path: fp32 residual stream + its bf16 fragment-major copy.
