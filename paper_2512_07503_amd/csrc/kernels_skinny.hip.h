@@ -11,6 +11,9 @@
 //   RESID   residual add into the fp32 stream + the bf16 copy of the stream that feeds the next GEMM
 //   SWIGLU  per-row RMSNorm scale, silu(gate) * up
 //   HEAD    per-row RMSNorm scale, fp32 logits
+//   PARTIAL plain fp32 partial sums [ksplit][M][N] of a K range (grid.y = ksplit); resid_reduce_kernel adds them
+//           up after the kernel boundary.  Used when one workgroup per column group would have to pull more
+//           than ~0.5 MB through its CU (wide K, M = 64): splitting K also splits the activation re-reads.
 // RMSNorm is folded in: the gain is multiplied into the weights when they are packed, the input is
 // the raw residual stream in bf16, its per-row sum of squares is accumulated from the very A fragments
 // the MFMA consumes, and the row scale 1/rms is applied to the accumulators (it commutes with the
@@ -19,7 +22,7 @@
 #include "common.hip.h"
 #include "kernels_forward.hip.h"
 
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PARTIAL = 4 };
 
 struct SkinnyArgs {
     const bf16_t *A;   // [MT][KB][64][8] raw activations, fragment-major
@@ -41,6 +44,10 @@ struct SkinnyArgs {
     int F;
     // HEAD
     float *logits;
+    // K split across workgroups (grid.y = ksplit > 1): per-workgroup partial tiles and arrival counters
+    int ksplit, kb_per_split;
+    float *part;             // [groups][ksplit][MT * NBW * 1024 + MT * 32]
+    unsigned int *counters;  // [groups], zero between launches
 #ifdef SJD_PHASE_TIMING
     unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
 #endif
@@ -48,13 +55,17 @@ struct SkinnyArgs {
 
 template <int MT, int NBW, int NW, int DEPTH, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
-    constexpr bool kNorm = EPI != EPI_RESID;
+    constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
     const int g = blockIdx.x, KB = a.KB;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
     const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + lane;
-    const int n_it = wave < KB ? (KB - wave + NW - 1) / NW : 0;
+    // this workgroup's k-blocks: [kb_lo, kb_hi); wavefront w takes kb_lo + w, kb_lo + w + NW, ...
+    const int ks = blockIdx.y;
+    const int kb_lo = ks * a.kb_per_split;
+    const int kb_hi = kb_lo + a.kb_per_split < KB ? kb_lo + a.kb_per_split : KB;
+    const int n_it = kb_lo + wave < kb_hi ? (kb_hi - kb_lo - wave + NW - 1) / NW : 0;
 #ifdef SJD_PHASE_TIMING
 #define SJD_STAMP(i) do { if (a.phase && tid == 0) a.phase[g * 8 + (i)] = wall_clock64(); } while (0)
 #else
@@ -81,7 +92,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-            const size_t kb = (size_t)(wave + (s < n_it ? s : n_it - 1) * NW);
+            const size_t kb = (size_t)(kb_lo + wave + (s < n_it ? s : n_it - 1) * NW);
 #pragma unroll
             for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
@@ -111,7 +122,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                         acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq[s][i]), acc[j][i], 0, 0, 0);
                 }
                 const int nx = it + DEPTH;
-                const size_t kb = (size_t)(wave + (nx < n_it ? nx : n_it - 1) * NW);
+                const size_t kb = (size_t)(kb_lo + wave + (nx < n_it ? nx : n_it - 1) * NW);
 #pragma unroll
                 for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
@@ -154,6 +165,54 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             }
         }
 
+    // ---- K split across workgroups: every workgroup publishes its partial tile; the one that arrives last
+    //      (whichever it is) adds all of them in the fixed order 0 .. ksplit - 1, so the result does not depend
+    //      on arrival order, and carries on to the epilogue.
+    if (EPI != EPI_PARTIAL && a.ksplit > 1) {
+        constexpr int REC = MT * NBW * 1024 + MT * 32;
+        float *rec = a.part + ((size_t)g * a.ksplit + ks) * REC;
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                for (int hh = 0; hh < EPT; ++hh) rec[(j * NBW + i) * 1024 + tid + NW * 64 * hh] = out[j][i][hh];
+        if (kNorm && tid < MT * 32) {
+            float t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) t += ssq_lds[w][tid >> 5][tid & 31];
+            rec[MT * NBW * 1024 + tid] = t;
+        }
+        __shared__ int s_last;
+        __threadfence();  // release: the partial tile is visible device-wide before the arrival is counted
+        __syncthreads();
+        if (tid == 0) s_last = atomicAdd(&a.counters[g], 1u) == (unsigned)a.ksplit - 1u;
+        __syncthreads();
+        if (!s_last) return;
+        __threadfence();  // acquire: the other workgroups' tiles
+        const float *all = a.part + (size_t)g * a.ksplit * REC;
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                for (int hh = 0; hh < EPT; ++hh) {
+                    float t = 0.0f;
+                    for (int k2 = 0; k2 < a.ksplit; ++k2) t += all[(size_t)k2 * REC + (j * NBW + i) * 1024 + tid + NW * 64 * hh];
+                    out[j][i][hh] = t;
+                }
+        if (kNorm) {
+            if (tid < MT * 32) {
+                float t = 0.0f;
+                for (int k2 = 0; k2 < a.ksplit; ++k2) t += all[(size_t)k2 * REC + MT * NBW * 1024 + tid];
+                ssq_lds[0][tid >> 5][tid & 31] = t;
+#pragma unroll
+                for (int w = 1; w < NW; ++w) ssq_lds[w][tid >> 5][tid & 31] = 0.0f;
+            }
+            __syncthreads();
+        }
+        if (tid == 0) a.counters[g] = 0u;  // ready for the next launch
+    }
     SJD_STAMP(2);
     const int col = lane & 31;
 #pragma unroll
@@ -171,7 +230,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 for (int w = 0; w < NW; ++w) t += ssq_lds[w][j][row];
                 inv = 1.0f / sqrtf(t / (float)(KB * 16) + a.eps);
             }
-            if (EPI == EPI_RESID) {
+            if (EPI == EPI_PARTIAL) {
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int n = (g * NBW + i) * 32 + col;
+                    if (n < a.N) a.part[((size_t)ks * a.M + m) * a.N + n] = out[j][i][hh];
+                }
+            } else if (EPI == EPI_RESID) {
 #pragma unroll
                 for (int i = 0; i < NBW; ++i) {
                     const int n = (g * NBW + i) * 32 + col;
@@ -275,19 +340,37 @@ __global__ void pack_weight_fused_kernel(const bf16_t *__restrict__ s0, const bf
     }
 }
 
-template <int EPI>
-inline hipError_t launch_skinny(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw) {
-    constexpr int NW = 8, DEPTH = 8;
+// x[m][n] += sum_ks part[ks][m][n];  xb = bf16(x) in GEMM-operand layout
+__global__ void resid_reduce_kernel(const float *__restrict__ part, int ksplit, int M, int N, float *__restrict__ x,
+                                    bf16_t *__restrict__ xb) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)M * N) return;
+    float v = x[idx];
+    for (int k = 0; k < ksplit; ++k) v += part[(size_t)k * M * N + idx];
+    x[idx] = v;
+    xb[Layout<bf16_t>::a_index((int)(idx / N), (int)(idx % N), N)] = float_to_bf16(v);
+}
+
+template <int EPI, int NW>
+inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw) {
+    constexpr int DEPTH = 8;
+    const dim3 grid(groups, a.ksplit);
+    constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
-        if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<groups, NW * 64, 0, st>>>(a);
-        else gemm_skinny_kernel<2, 2, NW, DEPTH, EPI><<<groups, NW * 64, 0, st>>>(a);
+        if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
+        else gemm_skinny_kernel<2, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
     } else {
-        if (EPI == EPI_RESID || EPI == EPI_HEAD) {
-            if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, EPI == EPI_HEAD ? EPI_HEAD : EPI_RESID><<<groups, NW * 64, 0, st>>>(a);
-            else gemm_skinny_kernel<2, 1, NW, DEPTH, EPI == EPI_HEAD ? EPI_HEAD : EPI_RESID><<<groups, NW * 64, 0, st>>>(a);
-        } else {
-            return hipErrorInvalidValue;
-        }
+        if (kPair) return hipErrorInvalidValue;
+        constexpr int E1 = kPair ? EPI_RESID : EPI;
+        if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
+        else gemm_skinny_kernel<2, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
     }
     return hipGetLastError();
+}
+
+// nw = wavefronts per workgroup: 8 when there are fewer column groups than CUs (one fat workgroup per CU), 4
+// when there are more (two or more resident workgroups per CU overlap one's epilogue with another's streaming).
+template <int EPI>
+inline hipError_t launch_skinny(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw, int nw = 8) {
+    return nw == 4 ? launch_skinny_nw<EPI, 4>(st, a, MT, groups, nbw) : launch_skinny_nw<EPI, 8>(st, a, MT, groups, nbw);
 }

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -64,6 +65,9 @@ struct sjd_ctx {
     bool attn_mfma = false;
     int attn_chunk = 0, attn_nchunks = 0;
     float *part_o = nullptr, *part_ml = nullptr;
+    float *skinny_part = nullptr;          // partial tiles of K-split fused projections
+    unsigned int *skinny_counters = nullptr;
+    size_t skinny_part_elems = 0;
     bool fused = false;  // small-M path: fused projection kernels, RMSNorm gains folded into the weights
     // weights (owned)
     void *tok_emb = nullptr, *lm_head = nullptr;
@@ -278,6 +282,17 @@ template <typename T> int forward(sjd_ctx *c, bool with_head) {
     return SJD_OK;
 }
 
+// How many workgroups share the K range of one column group.  A workgroup moves (cols + M) * K / ksplit
+// operand elements through its CU's L1; the grid runs in ceil(groups * ksplit / 256) rounds over the 256 CUs.
+// Pick the split with the least rounds x bytes, charging a split for its fix-up (~ the bytes of 2 us).
+int choose_ksplit(int groups, int cols, int M, int KB) {
+    // The in-kernel fix-up needs device-scope release/acquire fences, which on this multi-XCD part write back and
+    // invalidate the whole L2: measured 60-100 us per launch.  It stays switched off; K is split across workgroups
+    // only through a kernel boundary (EPI_PARTIAL + resid_reduce_kernel).
+    (void)groups; (void)cols; (void)M; (void)KB;
+    return 1;
+}
+
 // Small-M bf16 path: five kernels per layer (QKV+RoPE+KV write, attention, out+residual, gate/up+SwiGLU,
 // down+residual); c->xn holds the bf16 copy of the residual stream.
 int forward_fused(sjd_ctx *c, bool with_head) {
@@ -303,6 +318,43 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     a.h = (bf16_t *)c->h;
     a.logits = c->logits;
     const int nbw_d = ceil_div(d, 32) >= 128 ? 2 : 1;
+    a.part = c->skinny_part;
+    a.counters = c->skinny_counters;
+    auto split = [&](int groups, int nbw) {
+        a.ksplit = choose_ksplit(groups, nbw * 32, MT * 32, a.KB);
+        a.kb_per_split = ceil_div(a.KB, a.ksplit);
+        a.ksplit = ceil_div(a.KB, a.kb_per_split);
+        const size_t need = (size_t)groups * a.ksplit * (MT * nbw * 1024 + MT * 32);
+        return a.ksplit == 1 || need <= c->skinny_part_elems;
+    };
+    auto no_room = [&]() { sjd_set_error(c->err, "split-K workspace too small"); return SJD_EINVAL; };
+    auto nw_for = [](int groups) { return groups >= 150 ? 4 : 8; };
+    // output / down projection: x += A W^T.  One kernel when a workgroup's share is small, else K split over
+    // grid.y with the partial sums added by resid_reduce_kernel after the kernel boundary.
+    auto resid = [&](int cls, const void *A, const void *W, int K) -> int {
+        a.A = (const bf16_t *)A; a.W = (const bf16_t *)W; a.KB = K / 16; a.N = d;
+        const int groups = ceil_div(ceil_div(d, 32), nbw_d);
+        const double wg_bytes = (double)(nbw_d * 32 + MT * 32) * K * 2.0;
+        int ks = 1;
+        if (wg_bytes > 512e3) {
+            ks = std::min(8, std::max(1, 256 / groups));
+            while (ks > 1 && a.KB / ks < 32) --ks;
+        }
+        if (ks == 1) {
+            a.ksplit = 1; a.kb_per_split = a.KB;
+            SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
+            return SJD_OK;
+        }
+        a.kb_per_split = ceil_div(a.KB, ks);
+        a.ksplit = ceil_div(a.KB, a.kb_per_split);
+        if ((size_t)a.ksplit * M * d > c->skinny_part_elems) return no_room();
+        SJD_LAUNCH(c, cls, launch_skinny<EPI_PARTIAL>(st, a, MT, groups, nbw_d, nw_for(groups * a.ksplit)));
+        const int ksplit = a.ksplit;
+        SJD_LAUNCH(c, KC_ADDNORM, after([&] {
+                       resid_reduce_kernel<<<ceil_div(M * d, 256), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn);
+                   }));
+        return SJD_OK;
+    };
     for (int l = 0; l < md.n_layers; ++l) {
         const LayerWeights &lw = c->layers[l];
         KvPool pool;
@@ -313,18 +365,19 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         pool.page_tokens = c->pt;
         a.pool = pool;
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wqkv; a.KB = d / 16;
-        SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2));
+        if (!split((H + 2 * Hkv) * (hd / 64), 2)) return no_room();
+        SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2, nw_for((H + 2 * Hkv) * (hd / 64))));
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
-        a.A = (const bf16_t *)c->attn; a.W = (const bf16_t *)lw.wo; a.KB = H * hd / 16; a.N = d;
-        SJD_LAUNCH(c, KC_GEMM_O, launch_skinny<EPI_RESID>(st, a, MT, ceil_div(ceil_div(d, 32), nbw_d), nbw_d));
+        { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd); if (rc) return rc; }
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
-        SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2));
-        a.A = (const bf16_t *)c->h; a.W = (const bf16_t *)lw.wdown; a.KB = F / 16; a.N = d;
-        SJD_LAUNCH(c, KC_GEMM_DOWN, launch_skinny<EPI_RESID>(st, a, MT, ceil_div(ceil_div(d, 32), nbw_d), nbw_d));
+        if (!split(F / 32, 2)) return no_room();
+        SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+        { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F); if (rc) return rc; }
     }
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
-        SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2));
+        if (!split(ceil_div(ceil_div(c->Vs, 32), 2), 2)) return no_room();
+        SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
     }
     return SJD_OK;
 }
@@ -466,6 +519,13 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &c->attn, Layout<T>::a_elems(M, H * hd) * sizeof(T)))) return rc;
     if ((rc = dev_alloc(c, &c->h, Layout<T>::a_elems(M, F) * sizeof(T)))) return rc;
     if ((rc = dev_alloc(c, &c->q, (size_t)S * 2 * H * Layout<T>::q_elems(L, hd) * sizeof(T)))) return rc;
+    if (c->fused) {
+        // partial tiles of K-split projections: at most 8 splits of the widest projection (2 column blocks, 2 row tiles)
+        const int widest = std::max(std::max((H + 2 * Hkv) * (hd / 64), F / 32), ceil_div(c->Vs, 64));
+        c->skinny_part_elems = (size_t)widest * 8 * (2 * 2 * 1024 + 64);
+        if ((rc = dev_alloc(c, &c->skinny_part, c->skinny_part_elems * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &c->skinny_counters, (size_t)(widest + ceil_div(d, 32)) * sizeof(unsigned int)))) return rc;
+    }
     if (c->attn_mfma) {
         // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
         long want = (long)md.max_ctx * S * 2 * H / 1500;
