@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps in the CPU baseline (0 = sized to ~20 s)")
     ap.add_argument("--kernel-flags", type=int, default=0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; sequences are independent and would shard by prompt with no "
@@ -72,6 +74,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.calib_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     cfg = workload.get_config(args.config)
     arch, L, S, N, P = cfg["arch"], cfg["window"], cfg["n_seqs"], cfg["n_image"], cfg["prompt_len"]
     M = S * 2 * L
@@ -185,6 +194,16 @@ def main():
     if dom: roofline = {"kernel": dominant, "bound": "hbm", "achieved": dom.get("GBps"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4) if dom.get("GBps") else None, "traffic": None,
                 "avg_us": dom["avg_us"], "launches_per_step": dom["launches_per_step"]}
+    if dom:
+        try:   # HBM bytes per launch measured with rocprofv3 --pmc (profiles/pmc_traffic.json), if this config has them
+            pmc = json.load(open(os.path.join(ROOT, "profiles", "pmc_traffic.json"))).get(args.config, {}).get("kernels", {})
+            key = dominant if dominant in pmc else ("gemm_out+gemm_down" if dominant in ("gemm_out", "gemm_down") else None)
+            if key:
+                roofline["traffic"] = pmc[key]["fetch_bytes"] + pmc[key]["write_bytes"]
+                roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE scaled by a 256 MiB copy; bytes per launch"
+        except (OSError, ValueError, KeyError):
+            pass
+        roofline["algorithmic_bytes"] = algorithmic_bytes(dominant, cfg, M, mean_ctx)
     if dom and dominant.startswith("gemm") and M >= 320:      # above the ridge (~312 flop/B) the contraction is MFMA-bound
         roofline.update({"bound": "mfma", "achieved": dom["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(dom["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)})
