@@ -218,6 +218,85 @@ __global__ void sample_rows_kernel(SampleRowsArgs a) {
     if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
 }
 
+// Register-resident form for V <= 1024 * VPT: the guided logits of a row are read from HBM once and stay in
+// registers (thread t holds elements t, t + 1024, ...).  The K-th largest key is found one bit at a time, most
+// significant first: count the candidates whose next bit is 1; if at least `want` of them exist the K-th
+// largest has that bit set, otherwise it does not and `want` drops by that count.  32 counting rounds of a
+// wavefront ballots and one LDS exchange each, no atomics, exact.
+// adds one wave-uniform count per wavefront over the block; scratch alternates between rounds
+SJD_D uint32_t block_sum_wave_counts(uint32_t wave_count, uint32_t *scratch /* [16] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if (lane == 0) scratch[wave] = wave_count;
+    __syncthreads();
+    uint32_t t = 0;
+    for (int i = 0; i < nw; ++i) t += scratch[i];
+    return t;
+}
+
+template <int VPT>
+__global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a) {
+    const int r = blockIdx.x, s = r / a.L, k = r % a.L;
+    if (a.Le && k >= a.Le[s]) return;
+    const float *lc = a.lc_base + (long)s * a.seq_stride + (long)k * a.V;
+    const float *lu = a.lu_base + (long)s * a.seq_stride + (long)k * a.V;
+    const uint32_t par = a.step ? (*a.step & 1u) : 0u;
+    float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
+    const int V = a.V, tid = threadIdx.x;
+    __shared__ uint32_t cnt[2][16];
+    __shared__ uint32_t scratch32[17];
+    __shared__ uint64_t scratch64[17];
+
+    uint32_t key[VPT];  // order key of the guided logit; 0 (below every real key) past the end of the row
+    uint32_t kmax = 0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int v = tid + i * 1024;
+        key[i] = v < V ? order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t)) : 0u;
+        kmax = key[i] > kmax ? key[i] : kmax;
+    }
+    kmax = block_max_u32(kmax, scratch32);
+    const float m = key_to_float(kmax);
+
+    uint32_t thresh = 0;
+    if (a.top_k < V) {
+        uint32_t prefix = 0, want = (uint32_t)a.top_k;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t hi_mask = bit == 31 ? 0u : ~((2u << bit) - 1u);  // bits above `bit`
+            const uint32_t probe = prefix | (1u << bit);
+            uint32_t c = 0;  // wave-uniform: ballots, not shuffles
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) c += (uint32_t)__popcll(__ballot((key[i] & (hi_mask | (1u << bit))) == probe));
+            c = block_sum_wave_counts(c, cnt[bit & 1]);
+            if (c >= want) prefix = probe; else want -= c;
+        }
+        thresh = prefix;
+    }
+
+    uint64_t zsum = 0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int v = tid + i * 1024;
+        if (v < V) {
+            const float z = key_to_float(key[i]);
+            const float ev = key[i] >= thresh ? exp_neg(z - m) : 0.0f;
+            e[v] = ev;
+            zsum += weight_of(ev);
+        }
+    }
+    zsum = block_sum_u64(zsum, scratch64);
+    if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
+}
+
+hipError_t launch_sample_rows_any(hipStream_t st, const SampleRowsArgs &a, int rows) {
+    const int V = a.V;
+    if (V <= 1024 * 4) sample_rows_reg_kernel<4><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 16) sample_rows_reg_kernel<16><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 32) sample_rows_reg_kernel<32><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 64) sample_rows_reg_kernel<64><<<rows, 1024, 0, st>>>(a);
+    else sample_rows_kernel<<<rows, 1024, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 // --------------------------------------------------------------------------------- window set-up
 __global__ void init_window_kernel(DecideState d, uint64_t seed, int n_seqs, const int32_t *prompt_last,
                                    const int32_t *prompt_len, const int32_t *n_image) {
@@ -314,38 +393,66 @@ __global__ void verify_kernel(DecideState d, uint64_t seed) {
 }
 
 // ---------------------------------------------------- a12 / a13: the draws of a step (Eq. 3, Eq. 5)
-// Block-wide inverse CDF over integer weights weight(v), v in [0, V): returns the first v whose
-// inclusive prefix sum exceeds floor(u64 * total / 2^64), or -1 when total == 0.
+// Block-wide inverse CDF over integer weights weight(v), v in [0, V): returns the first v whose inclusive
+// prefix sum exceeds floor(u64 * total / 2^64), or -1 when total == 0.  Two levels: (1) each wavefront sums a
+// contiguous segment with coalesced reads, every thread scans the <= 16 segment totals and knows which segment
+// holds the target; (2) the whole block re-reads that segment, a few consecutive ids per thread, one
+// block-wide scan of the per-thread sums names the thread, which walks its ids.  Integer sums: exact.
+SJD_D uint64_t shfl_up_u64(uint64_t v, int delta) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_up(lo, delta, 64);
+    hi = __shfl_up(hi, delta, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 template <typename F>
-SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [blockDim.x + 2] shared */) {
-    const int nt = blockDim.x, tid = threadIdx.x;
-    const int chunk = (V + nt - 1) / nt;
-    const int v0 = tid * chunk, v1 = v0 + chunk < V ? v0 + chunk : V;
+SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20] shared */) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6, nt = blockDim.x;
+    // level 1: wavefront w owns the contiguous segment [w * seg, (w + 1) * seg), read 64 consecutive ids at a time
+    const int per = (V + nt - 1) / nt;          // ids per thread at level 2
+    const int seg = per * 64;
+    const int v0 = wave * seg, v1 = v0 + seg < V ? v0 + seg : V;
     uint64_t local = 0;
-    for (int v = v0; v < v1; ++v) local += weight(v);
+    for (int v = v0 + lane; v < v1; v += 64) local += weight(v);
+    for (int d = 32; d > 0; d >>= 1) local += shfl_down_u64(local, d);
     __syncthreads();
-    sums[tid] = local;
+    if (lane == 0) sums[wave] = local;
     __syncthreads();
-    if (tid == 0) {
-        uint64_t run = 0;
-        for (int i = 0; i < nt; ++i) { uint64_t t = sums[i]; sums[i] = run; run += t; }
-        sums[nt] = run;
-        sums[nt + 1] = (uint64_t)(int64_t)-1;
-    }
-    __syncthreads();
-    const uint64_t total = sums[nt];
+    uint64_t total = 0;
+    for (int i = 0; i < nw; ++i) total += sums[i];
     if (total == 0) return -1;
     const uint64_t target = mulhi64(u64, total);
-    const uint64_t excl = sums[tid];
-    if (excl <= target && target < excl + local) {
-        uint64_t prefix = excl;
-        for (int v = v0; v < v1; ++v) {
-            prefix += weight(v);
-            if (prefix > target) { sums[nt + 1] = (uint64_t)v; break; }
+    int hit_seg = 0;
+    uint64_t before = 0;
+    for (int i = 0; i < nw; ++i) {           // the segment whose range of prefix sums holds the target
+        if (before + sums[i] > target) { hit_seg = i; break; }
+        before += sums[i];
+    }
+    // level 2: the whole block re-reads that segment, thread t owning the `chunk` consecutive ids from s0 + t * chunk
+    const int s0 = hit_seg * seg, s1 = s0 + seg < V ? s0 + seg : V;
+    const int chunk = (seg + nt - 1) / nt;
+    const int c0 = s0 + tid * chunk, c1 = c0 + chunk < s1 ? c0 + chunk : s1;
+    uint64_t mine = 0;
+    for (int v = c0; v < c1; ++v) mine += weight(v);
+    uint64_t incl = mine;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t o = shfl_up_u64(incl, d);
+        if (lane >= d) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) sums[wave] = incl;
+    __syncthreads();
+    uint64_t excl = before + incl - mine;
+    for (int i = 0; i < wave; ++i) excl += sums[i];
+    if (excl <= target && target < excl + mine) {   // exactly one thread
+        uint64_t run = excl;
+        for (int v = c0; v < c1; ++v) {
+            run += weight(v);
+            if (run > target) { sums[18] = (uint64_t)v; break; }
         }
     }
     __syncthreads();
-    return (int)(int64_t)sums[nt + 1];
+    return (int)(int64_t)sums[18];
 }
 
 // One block per output row k of every sequence.  With a accepted drafts:
@@ -458,7 +565,6 @@ __global__ void philox_fill_kernel(uint64_t seed, uint32_t row, uint32_t seq, ui
     for (int j = 0; j < 4; ++j) out[4 * i + j] = w[j];
 }
 
-int rows_block(int V) { return V >= 16384 ? 1024 : 256; }
 
 }  // namespace
 
@@ -496,8 +602,7 @@ hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const Sampli
     a.top_k = sp.top_k;
     a.cfg_scale = sp.cfg_scale;
     a.inv_t = sp.inv_temperature;
-    sample_rows_kernel<<<n_seqs * d.L, rows_block(d.V), 0, st>>>(a);
-    return hipGetLastError();
+    return launch_sample_rows_any(st, a, n_seqs * d.L);
 }
 
 hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,
@@ -515,8 +620,7 @@ hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const flo
     a.top_k = sp.top_k;
     a.cfg_scale = sp.cfg_scale;
     a.inv_t = sp.inv_temperature;
-    sample_rows_kernel<<<rows, rows_block(V), 0, st>>>(a);
-    return hipGetLastError();
+    return launch_sample_rows_any(st, a, rows);
 }
 
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
@@ -525,8 +629,7 @@ hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingPar
 }
 
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    const int nt = 256;
-    draw_kernel<<<n_seqs * d.L, nt, (nt + 2) * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau);
+    draw_kernel<<<n_seqs * d.L, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau);
     return hipGetLastError();
 }
 
