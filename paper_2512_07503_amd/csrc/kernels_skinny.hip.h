@@ -28,6 +28,8 @@ struct SkinnyArgs {
     const bf16_t *A;   // [MT][KB][64][8] raw activations, fragment-major
     const bf16_t *W;   // [groups * NBW][KB][64][8]
     int M, KB;
+    int groups;        // column groups (set by the launcher)
+    int m_groups;      // row groups of MT * 32 rows, each run by its own workgroups over the same weights (M > 64)
     float eps;
     // RESID
     float *x;          // [M][N] fp32 residual stream, updated in place
@@ -58,9 +60,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
-    const int g = blockIdx.x, KB = a.KB;
+    // blockIdx.x enumerates (column group g, row group mg).  With several row groups the order is chosen so that
+    // the row groups of one column group are dispatched close together AND to the same XCD (workgroups go to
+    // XCDs round-robin by linear id): id = (g / 8) * 8 * m_groups + mg * 8 + g % 8, so they share the weights in L2.
+    int g = blockIdx.x, mg = 0;
+    if (a.m_groups > 1) {
+        const int id = blockIdx.x, span = 8 * a.m_groups;
+        if (a.groups % 8 == 0) {
+            g = (id / span) * 8 + (id & 7);
+            mg = (id % span) >> 3;
+        } else {
+            g = id / a.m_groups;
+            mg = id % a.m_groups;
+        }
+    }
+    const int KB = a.KB, m_base = mg * MT * 32;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
-    const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + lane;
+    const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + (size_t)mg * MT * KB * 64 + lane;
     // this workgroup's k-blocks: [kb_lo, kb_hi); wavefront w takes kb_lo + w, kb_lo + w + NW, ...
     const int ks = blockIdx.y;
     const int kb_lo = ks * a.kb_per_split;
@@ -221,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         for (int hh = 0; hh < EPT; ++hh) {
             const int v = wave + NW * hh;
             const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const int m = j * 32 + row;
+            const int m = m_base + j * 32 + row;
             if (m >= a.M) continue;
             float inv = 1.0f;
             if (kNorm) {
@@ -352,9 +368,11 @@ __global__ void resid_reduce_kernel(const float *__restrict__ part, int ksplit, 
 }
 
 template <int EPI, int NW>
-inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw) {
+inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int MT, int groups, int nbw) {
     constexpr int DEPTH = 8;
-    const dim3 grid(groups, a.ksplit);
+    SkinnyArgs a = a_in;
+    a.groups = groups;
+    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1), a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);

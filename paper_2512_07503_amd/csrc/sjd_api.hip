@@ -298,7 +298,9 @@ int choose_ksplit(int groups, int cols, int M, int KB) {
 int forward_fused(sjd_ctx *c, bool with_head) {
     const sjd_model_desc &md = c->md;
     const int M = c->n_seqs * 2 * c->L, d = md.d_model, H = md.n_heads, Hkv = md.n_kv_heads, hd = c->hd, F = md.d_ff;
-    const int MT = ceil_div(M, 32);
+    // up to 64 rows: one row group; more (a multiple of 64 by construction): row groups of 64 over the same weights
+    const int m_groups = M <= 64 ? 1 : M / 64;
+    const int MT = M <= 64 ? ceil_div(M, 32) : 2;
     hipStream_t st = c->stream;
     SJD_LAUNCH(c, KC_EMBED, after([&] {
                    embed_dual_kernel<<<M, 256, 0, st>>>((const bf16_t *)c->tok_emb, c->rm.row_tok, c->x, (bf16_t *)c->xn, d);
@@ -306,6 +308,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     SkinnyArgs a;
     memset(&a, 0, sizeof a);
     a.M = M;
+    a.m_groups = m_groups;
     a.eps = md.rms_eps;
     a.row_tok = c->rm.row_tok;
     a.row_pos = c->rm.row_pos;
@@ -337,7 +340,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         const double wg_bytes = (double)(nbw_d * 32 + MT * 32) * K * 2.0;
         int ks = 1;
         if (wg_bytes > 512e3) {
-            ks = std::min(8, std::max(1, 256 / groups));
+            ks = std::min(8, std::max(1, 256 / (groups * m_groups)));
             while (ks > 1 && a.KB / ks < 32) --ks;
         }
         if (ks == 1) {
@@ -685,7 +688,7 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
     const bool f32 = desc->dtype == SJD_F32;
     c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&
                    attention_mfma_supported(c->L, desc->n_heads, desc->n_kv_heads, c->hd, c->pt);
-    c->fused = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) && c->hd % 64 == 0 && c->S * 2 * c->L <= 64 &&
+    c->fused = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) && c->hd % 64 == 0 && (c->S * 2 * c->L <= 64 || (2 * c->L) % 64 == 0) &&
                desc->d_model % 32 == 0 && desc->d_ff % 32 == 0;
     rc = f32 ? copy_weights<float>(c, weights) : (c->fused ? copy_weights_fused(c, weights) : copy_weights<bf16_t>(c, weights));
     if (!rc) rc = f32 ? alloc_buffers<float>(c) : alloc_buffers<bf16_t>(c);
