@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps in the CPU baseline (0 = sized to ~20 s)")
     ap.add_argument("--kernel-flags", type=int, default=0)
+    ap.add_argument("--no-finish-image", action="store_true", help="do not run the image to its end for forwards/image")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -148,7 +149,7 @@ def main():
             prefill()
     ms_per_step = 1e3 * timed_s / timed_steps
     tokens_per_s = timed_tokens / timed_s
-    if not images_steps:   # finish the image (untimed) to know the forwards per image
+    if not images_steps and not args.no_finish_image:   # finish the image (untimed) to know the forwards per image
         while True:
             dec.step_raw(res)
             cur_steps += 1
@@ -156,7 +157,7 @@ def main():
                 break
         images_steps.append(cur_steps)
         prefill()
-    forwards_per_image = float(np.mean(images_steps))
+    forwards_per_image = float(np.mean(images_steps)) if images_steps else None
 
     # ---- per-kernel durations with HIP events on the library's stream, right after the timed region
     dec.trace(True)
@@ -223,6 +224,7 @@ def main():
                           reuse_tau=cfg["tau"], seed=cfg["seed"], max_seqs=S)
         c2 = [c[-sample_prompt:] for c in cond]
         u2 = [u[-sample_prompt:] for u in uncond]
+        print(f"cpu baseline: oracle prefill + steps on {cores} threads ...", file=sys.stderr, flush=True)
         tc = time.perf_counter()
         o.prefill(c2, u2, [N] * S)
         n_cpu, tok_cpu = 0, 0
@@ -230,6 +232,7 @@ def main():
         while True:
             r = o.step()
             n_cpu += 1
+            print(f"cpu baseline: step {n_cpu} done after {time.perf_counter() - tc:.0f} s", file=sys.stderr, flush=True)
             tok_cpu += sum(x["n_finalized"] for x in r)
             el = time.perf_counter() - tc
             if (args.cpu_steps and n_cpu >= args.cpu_steps) or (not args.cpu_steps and el > 15.0) or all(x["done"] for x in r):
@@ -251,7 +254,7 @@ def main():
                                f"tau {cfg['tau']}, random-init weights",
                    "window": L, "n_seqs": S, "gemm_rows": M, "head_alpha": round(cfg["head_alpha"], 4),
                    "head_alpha_calibrated": cfg["head_alpha_calibrated"]},
-        "forwards_per_image": round(forwards_per_image, 2),
+        "forwards_per_image": round(forwards_per_image, 2) if forwards_per_image else None,
         "tokens_per_step": round(float(np.mean(accepted_hist)) + 1.0, 4) if accepted_hist else None,
         "step_floor_ms_weights_at_hbm_peak": round(step_floor_ms, 4),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "setup_s": round(setup_s, 1),
