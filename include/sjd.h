@@ -49,7 +49,9 @@ enum sjd_dtype { SJD_F32 = 0, SJD_BF16 = 1 };
 /* kernel_flags bits */
 enum {
     SJD_KERNELS_REFERENCE = 1, /* use the plain (non-MFMA) GEMM and attention kernels */
-    SJD_NO_GRAPH = 2           /* never capture the step into a HIP graph             */
+    SJD_NO_GRAPH = 2,          /* never capture the step into a HIP graph             */
+    SJD_KERNELS_ROWGROUPS = 4  /* bf16, >= 256 rows: keep the 64-row-group streaming projection
+                                * kernels instead of the LDS-staged tile kernels       */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

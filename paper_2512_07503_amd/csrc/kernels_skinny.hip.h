@@ -55,6 +55,99 @@ struct SkinnyArgs {
 #endif
 };
 
+// Where row m of the QKV projection goes.  The operand layouts of queries, keys and values are all of the form
+// f(row) + g(head dimension), so everything that depends on the row alone is worked out once per row:
+struct QkvRow {
+    int pos;    // absolute position (rotary angle), -1 for a row that is not computed
+    int q_off;  // element offset of this row in the query buffer of head 0: sequence segment and window index
+    int page;   // KV page of the position
+    int k_off;  // row part of the element offset inside a (page, head) block of keys
+    int v_off;  // same for values
+};
+SJD_D QkvRow qkv_row(const SkinnyArgs &a, int m) {
+    QkvRow r;
+    if (a.row_tok[m] < 0) {
+        r.pos = -1; r.q_off = 0; r.page = 0; r.k_off = 0; r.v_off = 0;
+        return r;
+    }
+    const int seg = m / a.L, i_win = m % a.L;
+    r.pos = a.row_pos[m];
+    r.q_off = seg * a.H * (int)Layout<bf16_t>::q_elems(a.L, a.hd) + (int)Layout<bf16_t>::q_index(i_win, 0, a.hd);
+    r.page = a.pool.page_table[seg * a.pool.pages_per_seg + r.pos / a.pool.page_tokens];
+    const int t = r.pos % a.pool.page_tokens;
+    r.k_off = (int)Layout<bf16_t>::k_index(t, 0, a.hd);
+    r.v_off = (int)Layout<bf16_t>::v_index(t, 0, a.hd);
+    return r;
+}
+// Column group g = (head, sub-block of 32 dimensions); v0 / v1 are dimensions j0 = 32 sub + col and j0 + hd / 2 of
+// that head (a rotary pair): rotate q and k, then queries to the attention operand layout, keys / values into
+// their page.
+SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float v0, float v1) {
+    if (r.pos < 0) return;
+    const int pairs = a.hd >> 6;
+    const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
+    const int j0 = sub * 32 + col, j1 = j0 + half;
+    if (head < a.H + a.Hkv) {
+        const float c = a.rope_cos[(size_t)r.pos * half + j0], s = a.rope_sin[(size_t)r.pos * half + j0];
+        const float r0 = v0 * c - v1 * s, r1 = v1 * c + v0 * s;
+        v0 = r0;
+        v1 = r1;
+    }
+    if (head < a.H) {
+        bf16_t *dst = a.q_out + (size_t)head * Layout<bf16_t>::q_elems(a.L, a.hd) + r.q_off;
+        dst[Layout<bf16_t>::q_index(0, j0, a.hd)] = float_to_bf16(v0);
+        dst[Layout<bf16_t>::q_index(0, j1, a.hd)] = float_to_bf16(v1);
+    } else {
+        const size_t blk = (size_t)a.pool.page_tokens * a.hd;
+        if (head < a.H + a.Hkv) {
+            bf16_t *dst = (bf16_t *)a.pool.k + ((size_t)r.page * a.Hkv + (head - a.H)) * blk + r.k_off;
+            dst[Layout<bf16_t>::k_index(0, j0, a.hd)] = float_to_bf16(v0);
+            dst[Layout<bf16_t>::k_index(0, j1, a.hd)] = float_to_bf16(v1);
+        } else {
+            bf16_t *dst = (bf16_t *)a.pool.v + ((size_t)r.page * a.Hkv + (head - a.H - a.Hkv)) * blk + r.v_off;
+            dst[Layout<bf16_t>::v_index(0, j0, a.hd)] = float_to_bf16(v0);
+            dst[Layout<bf16_t>::v_index(0, j1, a.hd)] = float_to_bf16(v1);
+        }
+    }
+}
+
+// One output element pair of the projection epilogues: row m, column `col` of the NBW column blocks of group g
+// (val[i] = block g * NBW + i), inv = 1 / rms of row m (1 where the epilogue does not normalise).
+template <int EPI, int NBW>
+SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, const float (&val)[NBW], float inv) {
+    if constexpr (EPI == EPI_PARTIAL) {
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            const int n = (g * NBW + i) * 32 + col;
+            if (n < a.N) a.part[((size_t)ks * a.M + m) * a.N + n] = val[i];
+        }
+    } else if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            const int n = (g * NBW + i) * 32 + col;
+            if (n < a.N) {
+                const float nv = a.x[(size_t)m * a.N + n] + val[i];
+                a.x[(size_t)m * a.N + n] = nv;
+                a.xb[Layout<bf16_t>::a_index(m, n, a.N)] = float_to_bf16(nv);
+            }
+        }
+    } else if constexpr (EPI == EPI_HEAD) {
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            const int n = (g * NBW + i) * 32 + col;
+            if (n < a.N) a.logits[(size_t)m * a.N + n] = val[i] * inv;
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // tile 0 = gate columns [32 g, 32 g + 32), tile 1 = the matching up columns
+        const float gt = val[0] * inv, up = val[1] * inv;
+        const int n = g * 32 + col;
+        if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
+    } else {  // EPI_QKV
+        const QkvRow r = qkv_row(a, m);
+        qkv_store(a, r, g, col, val[0] * inv, val[1] * inv);
+    }
+}
+
 template <int MT, int NBW, int NW, int DEPTH, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
@@ -246,65 +339,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 for (int w = 0; w < NW; ++w) t += ssq_lds[w][j][row];
                 inv = 1.0f / sqrtf(t / (float)(KB * 16) + a.eps);
             }
-            if (EPI == EPI_PARTIAL) {
+            float vals[NBW];
 #pragma unroll
-                for (int i = 0; i < NBW; ++i) {
-                    const int n = (g * NBW + i) * 32 + col;
-                    if (n < a.N) a.part[((size_t)ks * a.M + m) * a.N + n] = out[j][i][hh];
-                }
-            } else if (EPI == EPI_RESID) {
-#pragma unroll
-                for (int i = 0; i < NBW; ++i) {
-                    const int n = (g * NBW + i) * 32 + col;
-                    if (n < a.N) {
-                        const float nv = a.x[(size_t)m * a.N + n] + out[j][i][hh];
-                        a.x[(size_t)m * a.N + n] = nv;
-                        a.xb[Layout<bf16_t>::a_index(m, n, a.N)] = float_to_bf16(nv);
-                    }
-                }
-            } else if (EPI == EPI_HEAD) {
-#pragma unroll
-                for (int i = 0; i < NBW; ++i) {
-                    const int n = (g * NBW + i) * 32 + col;
-                    if (n < a.N) a.logits[(size_t)m * a.N + n] = out[j][i][hh] * inv;
-                }
-            } else if (EPI == EPI_SWIGLU) {
-                // tile 0 = gate columns [32 g, 32 g + 32), tile 1 = the matching up columns
-                const float gt = out[j][0][hh] * inv, up = out[j][1][hh] * inv;
-                const int n = g * 32 + col;
-                if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
-            } else {  // EPI_QKV: group g = (head hh_, sub-block sub); tiles = dims j0 = 32 sub + col and j0 + hd / 2
-                if (a.row_tok[m] < 0) continue;
-                const int pairs = a.hd >> 6;
-                const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
-                const int j0 = sub * 32 + col, j1 = j0 + half;
-                const int seg = m / a.L, i_win = m % a.L, pos = a.row_pos[m];
-                float v0 = out[j][0][hh] * inv, v1 = out[j][1][hh] * inv;
-                if (head < a.H + a.Hkv) {
-                    const float c = a.rope_cos[(size_t)pos * half + j0], s = a.rope_sin[(size_t)pos * half + j0];
-                    const float r0 = v0 * c - v1 * s, r1 = v1 * c + v0 * s;
-                    v0 = r0;
-                    v1 = r1;
-                }
-                if (head < a.H) {
-                    bf16_t *dst = a.q_out + ((size_t)seg * a.H + head) * Layout<bf16_t>::q_elems(a.L, a.hd);
-                    dst[Layout<bf16_t>::q_index(i_win, j0, a.hd)] = float_to_bf16(v0);
-                    dst[Layout<bf16_t>::q_index(i_win, j1, a.hd)] = float_to_bf16(v1);
-                } else {
-                    const int page = a.pool.page_table[seg * a.pool.pages_per_seg + pos / a.pool.page_tokens];
-                    const int t = pos % a.pool.page_tokens;
-                    const size_t blk = (size_t)a.pool.page_tokens * a.hd;
-                    if (head < a.H + a.Hkv) {
-                        bf16_t *dst = (bf16_t *)a.pool.k + ((size_t)page * a.Hkv + (head - a.H)) * blk;
-                        dst[Layout<bf16_t>::k_index(t, j0, a.hd)] = float_to_bf16(v0);
-                        dst[Layout<bf16_t>::k_index(t, j1, a.hd)] = float_to_bf16(v1);
-                    } else {
-                        bf16_t *dst = (bf16_t *)a.pool.v + ((size_t)page * a.Hkv + (head - a.H - a.Hkv)) * blk;
-                        dst[Layout<bf16_t>::v_index(t, j0, a.hd)] = float_to_bf16(v0);
-                        dst[Layout<bf16_t>::v_index(t, j1, a.hd)] = float_to_bf16(v1);
-                    }
-                }
-            }
+            for (int i = 0; i < NBW; ++i) vals[i] = out[j][i][hh];
+            skinny_epilogue<EPI, NBW>(a, ks, m, g, col, vals, inv);
         }
     SJD_STAMP(3);
 }

@@ -16,6 +16,7 @@
 #include "kernels_forward.hip.h"
 #include "kernels_gemm.hip.h"
 #include "kernels_skinny.hip.h"
+#include "kernels_tile.hip.h"
 
 void sjd_set_error(char *buf, const char *fmt, ...) {
     if (!buf) return;
@@ -332,10 +333,30 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     };
     auto no_room = [&]() { sjd_set_error(c->err, "split-K workspace too small"); return SJD_EINVAL; };
     auto nw_for = [](int groups) { return groups >= 150 ? 4 : 8; };
+    // many rows: LDS-staged 256 x 128 tiles (the projections are a dense contraction there, not a weight stream)
+    const bool tile = M >= TILE_M && !(md.kernel_flags & SJD_KERNELS_ROWGROUPS);
     // output / down projection: x += A W^T.  One kernel when a workgroup's share is small, else K split over
     // grid.y with the partial sums added by resid_reduce_kernel after the kernel boundary.
     auto resid = [&](int cls, const void *A, const void *W, int K) -> int {
         a.A = (const bf16_t *)A; a.W = (const bf16_t *)W; a.KB = K / 16; a.N = d;
+        if (tile) {
+            const int n_blocks = ceil_div(d, 64) * 2, wgs = ceil_div(n_blocks, 4) * ceil_div(M, TILE_M);
+            int ks = std::min(8, std::max(1, 256 / wgs));
+            while (ks > 1 && a.KB / ks < 32) --ks;
+            a.kb_per_split = ceil_div(a.KB, ks);
+            a.ksplit = ceil_div(a.KB, a.kb_per_split);
+            if (a.ksplit == 1) {
+                SJD_LAUNCH(c, cls, launch_tile<EPI_RESID>(st, a, n_blocks));
+                return SJD_OK;
+            }
+            if ((size_t)a.ksplit * M * d > c->skinny_part_elems) return no_room();
+            SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks));
+            const int ksplit = a.ksplit;
+            SJD_LAUNCH(c, KC_ADDNORM, after([&] {
+                           resid_reduce_kernel<<<ceil_div(M * d, 256), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn);
+                       }));
+            return SJD_OK;
+        }
         const int groups = ceil_div(ceil_div(d, 32), nbw_d);
         const double wg_bytes = (double)(nbw_d * 32 + MT * 32) * K * 2.0;
         int ks = 1;
@@ -368,19 +389,34 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         pool.page_tokens = c->pt;
         a.pool = pool;
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wqkv; a.KB = d / 16;
-        if (!split((H + 2 * Hkv) * (hd / 64), 2)) return no_room();
-        SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2, nw_for((H + 2 * Hkv) * (hd / 64))));
+        if (tile) {
+            a.ksplit = 1; a.kb_per_split = a.KB;
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2));
+        } else {
+            if (!split((H + 2 * Hkv) * (hd / 64), 2)) return no_room();
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2, nw_for((H + 2 * Hkv) * (hd / 64))));
+        }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
         { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd); if (rc) return rc; }
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
-        if (!split(F / 32, 2)) return no_room();
-        SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+        if (tile) {
+            a.ksplit = 1; a.kb_per_split = a.KB;
+            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2));
+        } else {
+            if (!split(F / 32, 2)) return no_room();
+            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+        }
         { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F); if (rc) return rc; }
     }
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
-        if (!split(ceil_div(ceil_div(c->Vs, 32), 2), 2)) return no_room();
-        SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
+        if (tile) {
+            a.ksplit = 1; a.kb_per_split = a.KB;
+            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2));
+        } else {
+            if (!split(ceil_div(ceil_div(c->Vs, 32), 2), 2)) return no_room();
+            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
+        }
     }
     return SJD_OK;
 }
@@ -525,7 +561,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
     if (c->fused) {
         // partial tiles of K-split projections: at most 8 splits of the widest projection (2 column blocks, 2 row tiles)
         const int widest = std::max(std::max((H + 2 * Hkv) * (hd / 64), F / 32), ceil_div(c->Vs, 64));
-        c->skinny_part_elems = (size_t)widest * 8 * (2 * 2 * 1024 + 64);
+        c->skinny_part_elems = std::max((size_t)widest * 8 * (2 * 2 * 1024 + 64), (size_t)8 * M * d);
         if ((rc = dev_alloc(c, &c->skinny_part, c->skinny_part_elems * sizeof(float)))) return rc;
         if ((rc = dev_alloc(c, &c->skinny_counters, (size_t)(widest + ceil_div(d, 32)) * sizeof(unsigned int)))) return rc;
     }

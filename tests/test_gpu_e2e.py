@@ -38,7 +38,8 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 
 
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
-                                        ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1)])
+                                        ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
+                                        ("small_tile", 0), ("small_tile", 4)])
 def test_small_models_step_by_step(oracle, name, flags):
     cfg = workload.get_config(name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, kernel_flags=flags, head_alpha=6.0, std=0.08, random_gains=True)
@@ -77,7 +78,7 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
 
 
 @pytest.mark.parametrize("name,layers,prompt,steps,S", [("cfg1", 36, 24, 3, 1), ("cfg1", 2, 120, 40, 1),
-                                                        ("cfg2", 2, 64, 3, 1), ("cfg3", 2, 64, 3, 1), ("cfg4", 2, 64, 3, 3)])
+                                                        ("cfg2", 2, 64, 3, 1), ("cfg3", 2, 64, 3, 1), ("cfg4", 2, 64, 3, 3), ("cfg4", 2, 64, 2, 5)])
 def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
