@@ -50,8 +50,11 @@ enum sjd_dtype { SJD_F32 = 0, SJD_BF16 = 1 };
 enum {
     SJD_KERNELS_REFERENCE = 1, /* use the plain (non-MFMA) GEMM and attention kernels */
     SJD_NO_GRAPH = 2,          /* never capture the step into a HIP graph             */
-    SJD_KERNELS_ROWGROUPS = 4  /* bf16, >= 256 rows: keep the 64-row-group streaming projection
+    SJD_KERNELS_ROWGROUPS = 4, /* bf16, >= 256 rows: keep the 64-row-group streaming projection
                                 * kernels instead of the LDS-staged tile kernels       */
+    SJD_ATTENTION_CHUNKED = 8  /* bf16: always split the context over workgroups and merge
+                                * in a second kernel, also where one workgroup per head
+                                * would do (short contexts)                            */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

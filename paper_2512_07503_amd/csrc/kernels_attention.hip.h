@@ -120,21 +120,13 @@ struct AttnArgs {
     float scale_log2e;       // 1 / sqrt(hd) * log2(e)
 };
 
+// One wavefront's pass over the 32-token blocks t_begin, t_begin + t_stride, ... < t_end of (segment seg, query
+// head h): leaves the unnormalised O^T in o, the running maximum (base-2 logits) in m_run and this lane's half of
+// the running sum in l_run; query = lane % 32.
 template <int HD>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
+SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int t_begin, int t_end, int t_stride, int kv, int n_tot, int lane,
+                          f32x16 (&o)[HD / 32], float &m_run, float &l_run) {
     constexpr int KF = HD / 16, DB = HD / 32;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int G = a.H / a.Hkv;
-    const int c = blockIdx.x, kvh = blockIdx.y, seg = blockIdx.z;
-    const int h = kvh * G + wave;
-    const int n_act = a.seg_n[seg];
-    const int kv = a.seg_kv[seg];
-    const int n_tot = n_act > 0 ? kv + n_act : 0;
-    const int t_begin = c * a.chunk;
-    if (t_begin >= n_tot) return;
-    const int t_end = t_begin + a.chunk < n_tot ? t_begin + a.chunk : n_tot;
-
     const u32x4 *qp = reinterpret_cast<const u32x4 *>(a.q + ((size_t)seg * a.H + h) * Layout<bf16_t>::q_elems(a.L, HD)) + lane;
     u32x4 qf[KF];
 #pragma unroll
@@ -152,12 +144,13 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
                (size_t)((t0 % ptok) >> 5) * 2 * DB * 64 + lane;
     };
 
-    f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;  // per query (= lane % 32); l_run is this lane's half only
+    m_run = -INFINITY;
+    l_run = 0.0f;
+    if (t_begin >= t_end) return;
     const int query = lane & 31;
 
     u32x4 kf[KF], vf[2 * DB];
@@ -170,7 +163,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
         for (int f = 0; f < 2 * DB; ++f) vf[f] = vp[f * 64];
     }
     __builtin_amdgcn_sched_barrier(0);
-    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+    for (int t0 = t_begin; t0 < t_end; t0 += t_stride) {
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.0f;
@@ -178,7 +171,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
         for (int kb = 0; kb < KF; ++kb)
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kb]), __builtin_bit_cast(bf16x8, qf[kb]), s, 0, 0, 0);
         // next block's keys while this block's softmax and PV run (clamped to the last block: a cache hit)
-        const int tn = t0 + 32 < t_end ? t0 + 32 : t0;
+        const int tn = t0 + t_stride < t_end ? t0 + t_stride : t0;
         {
             const u32x4 *kp = kfrag(tn);
 #pragma unroll
@@ -227,6 +220,26 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
+    constexpr int DB = HD / 32;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int G = a.H / a.Hkv;
+    const int c = blockIdx.x, kvh = blockIdx.y, seg = blockIdx.z;
+    const int h = kvh * G + wave;
+    const int n_act = a.seg_n[seg];
+    const int kv = a.seg_kv[seg];
+    const int n_tot = n_act > 0 ? kv + n_act : 0;
+    const int t_begin = c * a.chunk;
+    if (t_begin >= n_tot) return;
+    const int t_end = t_begin + a.chunk < n_tot ? t_begin + a.chunk : n_tot;
+    f32x16 o[DB];
+    float m_run, l_run;
+    attention_wave<HD>(a, seg, h, kvh, t_begin, t_end, 32, kv, n_tot, lane, o, m_run, l_run);
+    const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
     const size_t slot = ((size_t)seg * a.H + h) * a.n_chunks + c;
     float *po = a.part_o + slot * 32 * HD + (size_t)query * HD;
@@ -237,6 +250,68 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
     if (lane < 32) {
         a.part_ml[slot * 64 + query] = m_run;
         a.part_ml[slot * 64 + 32 + query] = l_run;
+    }
+}
+
+// Short contexts (keys + values of one head within a few hundred KB): one workgroup per (segment, query head) does
+// the whole softmax.  Its NS wavefronts take the 32-token blocks round-robin, then merge through LDS:
+// out = sum_w 2^(m_w - m) O_w / sum_w 2^(m_w - m) l_w, written straight into the next GEMM's operand layout.
+// No partial results go to HBM and no second kernel is launched.
+template <int HD, int NS>
+__global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) {
+    constexpr int DB = HD / 32, EPT = 16 / NS;
+    static_assert(16 % NS == 0, "NS must divide 16");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = blockIdx.x, seg = blockIdx.y;
+    const int kvh = h / (a.H / a.Hkv);
+    const int n_act = a.seg_n[seg];
+    const int kv = a.seg_kv[seg];
+    const int n_tot = n_act > 0 ? kv + n_act : 0;
+    f32x16 o[DB];
+    float m_run, l_run;
+    attention_wave<HD>(a, seg, h, kvh, 32 * wave, n_tot, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
+    const int query = lane & 31;
+    l_run += __shfl_xor(l_run, 32, 64);
+
+    __shared__ float ml[NS][2][32];
+    __shared__ float red[NS][16][64];
+    if (lane < 32) {
+        ml[wave][0][query] = m_run;
+        ml[wave][1][query] = l_run;
+    }
+    __syncthreads();
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NS; ++w) m_all = fmaxf(m_all, ml[w][0][query]);
+    const float m_use = m_all == -INFINITY ? 0.0f : m_all;
+    float denom = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NS; ++w) denom += exp2f(ml[w][0][query] - m_use) * ml[w][1][query];
+    const float scale = exp2f(m_run - m_use);  // 0 for a wavefront that saw nothing
+    const int m = seg * a.L + query;
+    const bool row = query < a.L;
+    const bool active = row && a.row_tok[m] >= 0 && denom > 0.0f;
+    const float inv = active ? 1.0f / denom : 0.0f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][v][lane] = o[db][v] * scale;
+        __syncthreads();
+#pragma unroll
+        for (int hh = 0; hh < EPT; ++hh) {
+            const int v = wave + NS * hh;
+            float t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NS; ++w) t += red[w][v][lane];
+            t = active ? t * inv : 0.0f;  // 0 * inf (an idle row's garbage) must not become NaN
+            const int j = db * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (row) {
+                if (a.out_act) a.out_act[Layout<bf16_t>::a_index(m, h * HD + j, a.H * HD)] = float_to_bf16(t);
+                if (a.out_plain) a.out_plain[((size_t)m * a.H + h) * HD + j] = t;
+            }
+        }
     }
 }
 
@@ -267,8 +342,17 @@ inline bool attention_mfma_supported(int L, int H, int Hkv, int hd, int page_tok
     return L <= 32 && (hd == 64 || hd == 128) && H / Hkv <= 4 && page_tokens % 32 == 0;
 }
 
-// n_segments segments of L rows each; max_tokens bounds cache + window of any segment
-inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n_segments) {
+// One workgroup per (segment, head) pays while the keys and values of a head are a small stream for one CU.
+inline bool attention_onepass_pays(int max_tokens, int hd) { return (size_t)max_tokens * hd * 4 <= 256 * 1024; }
+
+// n_segments segments of L rows each.  onepass: contexts short enough for one workgroup per (segment, head).
+inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n_segments, bool onepass = false) {
+    if (onepass) {
+        const dim3 grid(a.H, n_segments);
+        if (a.hd == 64) attention_onepass_kernel<64, 8><<<grid, 512, 0, st>>>(a);
+        else attention_onepass_kernel<128, 8><<<grid, 512, 0, st>>>(a);
+        return hipGetLastError();
+    }
     dim3 grid(a.n_chunks, a.Hkv, n_segments);
     const int G = a.H / a.Hkv;
     if (a.hd == 64) attention_mfma_kernel<64><<<grid, G * 64, 0, st>>>(a);

@@ -65,6 +65,7 @@ struct sjd_ctx {
     bool prefilled = false, all_done = false;
     bool attn_mfma = false;
     int attn_chunk = 0, attn_nchunks = 0;
+    bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
     float *part_o = nullptr, *part_ml = nullptr;
     float *skinny_part = nullptr;          // partial tiles of K-split fused projections
     unsigned int *skinny_counters = nullptr;
@@ -225,7 +226,7 @@ template <> int run_attention<bf16_t>(sjd_ctx *c, const KvPool &pool, int M) {
     a.chunk = c->attn_chunk;
     a.n_chunks = c->attn_nchunks;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)c->hd));
-    SJD_LAUNCH(c, KC_ATTENTION, launch_attention_mfma(c->stream, a, M / c->L));
+    SJD_LAUNCH(c, KC_ATTENTION, launch_attention_mfma(c->stream, a, M / c->L, c->attn_onepass));
     return SJD_OK;
 }
 
@@ -571,6 +572,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         int chunk = (int)((want + 63) / 64) * 64;
         if (chunk < 128) chunk = 128;
         c->attn_chunk = chunk;
+        c->attn_onepass = !(md.kernel_flags & SJD_ATTENTION_CHUNKED) && attention_onepass_pays(md.max_ctx, hd);
         c->attn_nchunks = ceil_div(md.max_ctx, chunk);
         const size_t slots = (size_t)S * 2 * H * c->attn_nchunks;
         if ((rc = dev_alloc(c, &c->part_o, slots * 32 * hd * sizeof(float)))) return rc;

@@ -115,7 +115,7 @@ int op_attention(hipStream_t st, int flags, const void *q, const void *k, const 
     }
     OP_TRY(hipEventRecord(s.ev0, st));
     for (int r = 0; r < repeat; ++r) {
-        if (mfma) OP_TRY(launch_attention_mfma(st, a, 1));
+        if (mfma) OP_TRY(launch_attention_mfma(st, a, 1, !(flags & SJD_ATTENTION_CHUNKED) && attention_onepass_pays(n_tok, hd)));
         else OP_TRY(launch_attention_reference<T>(st, qp, pool, row_tok, seg_kv, (T *)nullptr, out, n, n, H, Hkv, hd, n_tok + 1));
     }
     OP_TRY(hipEventRecord(s.ev1, st));

@@ -39,7 +39,7 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
                                         ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
-                                        ("small_tile", 0), ("small_tile", 4)])
+                                        ("small_tile", 0), ("small_tile", 4), ("small_fused64", 8)])
 def test_small_models_step_by_step(oracle, name, flags):
     cfg = workload.get_config(name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, kernel_flags=flags, head_alpha=6.0, std=0.08, random_gains=True)
@@ -77,16 +77,20 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
     print("cfg0 steps", steps, "worst logits error abs/rel:", worst)
 
 
-@pytest.mark.parametrize("name,layers,prompt,steps,S", [("cfg1", 36, 24, 3, 1), ("cfg1", 2, 120, 40, 1),
-                                                        ("cfg2", 2, 64, 3, 1), ("cfg3", 2, 64, 3, 1), ("cfg4", 2, 64, 3, 3), ("cfg4", 2, 64, 2, 5)])
-def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S):
+@pytest.mark.parametrize("name,layers,prompt,steps,S,flags", [("cfg1", 36, 24, 3, 1, 0), ("cfg1", 2, 120, 40, 1, 0),
+                                                              ("cfg2", 2, 64, 3, 1, 0), ("cfg3", 2, 64, 3, 1, 0),
+                                                              ("cfg4", 2, 64, 3, 3, 0), ("cfg4", 2, 64, 2, 5, 0),
+                                                              # the chunk + merge attention kernels the full-length
+                                                              # 7B-class contexts use (these short twins would not)
+                                                              ("cfg1", 2, 120, 6, 1, 8), ("cfg3", 2, 64, 3, 1, 8)])
+def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
     cfg = workload.get_config(name)
     arch = dict(cfg["arch"], n_layers=layers)
     w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16")
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S,
-                                          n_image=min(cfg["n_image"], 200))
+                                          n_image=min(cfg["n_image"], 200), kernel_flags=flags)
     worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)
     print(name, layers, "worst logits error abs/rel:", worst)
 

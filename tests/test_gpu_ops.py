@@ -114,6 +114,10 @@ def test_window_attention_fp32(sjd, n, ctx, H, Hkv, hd):
 @pytest.mark.parametrize("n,ctx,H,Hkv,hd,flags", [(16, 0, 2, 2, 64, 1), (16, 119, 20, 20, 64, 1), (32, 700, 8, 8, 128, 1),
                                                    (32, 300, 8, 2, 128, 1), (1, 77, 4, 4, 64, 1), (16, 0, 2, 2, 64, 0),
                                                    (16, 119, 20, 20, 64, 0), (32, 700, 8, 8, 128, 0), (32, 300, 8, 2, 128, 0),
-                                                   (1, 77, 4, 4, 64, 0), (5, 1000, 2, 1, 32, 0), (32, 64, 4, 4, 128, 0)])
+                                                   (1, 77, 4, 4, 64, 0), (5, 1000, 2, 1, 32, 0), (32, 64, 4, 4, 128, 0),
+                                                   # one workgroup per head at the full LlamaGen-shaped context; the same
+                                                   # small cases through the chunk + merge kernels (flag 8)
+                                                   (16, 690, 20, 20, 64, 0), (16, 690, 20, 20, 64, 8), (16, 119, 20, 20, 64, 8),
+                                                   (32, 300, 8, 2, 128, 8), (1, 77, 4, 4, 64, 8), (16, 0, 2, 2, 64, 8)])
 def test_window_attention_bf16(sjd, n, ctx, H, Hkv, hd, flags):
     _attention_case(sjd, n, ctx, H, Hkv, hd, "bf16", flags=flags)
