@@ -82,13 +82,23 @@ SJD_D QkvRow qkv_row(const SkinnyArgs &a, int m) {
 // Column group g = (head, sub-block of 32 dimensions); v0 / v1 are dimensions j0 = 32 sub + col and j0 + hd / 2 of
 // that head (a rotary pair): rotate q and k, then queries to the attention operand layout, keys / values into
 // their page.
-SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float v0, float v1) {
+// (cos, sin) of the rotation that qkv_store applies to this element pair: (1, 0) for value heads and idle rows
+SJD_D void qkv_rotation(const SkinnyArgs &a, const QkvRow &r, int g, int col, float &c, float &s) {
+    const int pairs = a.hd >> 6;
+    const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
+    c = 1.0f;
+    s = 0.0f;
+    if (r.pos >= 0 && head < a.H + a.Hkv) {
+        c = a.rope_cos[(size_t)r.pos * half + sub * 32 + col];
+        s = a.rope_sin[(size_t)r.pos * half + sub * 32 + col];
+    }
+}
+SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float v0, float v1, float c, float s) {
     if (r.pos < 0) return;
     const int pairs = a.hd >> 6;
     const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
     const int j0 = sub * 32 + col, j1 = j0 + half;
-    if (head < a.H + a.Hkv) {
-        const float c = a.rope_cos[(size_t)r.pos * half + j0], s = a.rope_sin[(size_t)r.pos * half + j0];
+    {
         const float r0 = v0 * c - v1 * s, r1 = v1 * c + v0 * s;
         v0 = r0;
         v1 = r1;
@@ -113,8 +123,10 @@ SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float
 
 // One output element pair of the projection epilogues: row m, column `col` of the NBW column blocks of group g
 // (val[i] = block g * NBW + i), inv = 1 / rms of row m (1 where the epilogue does not normalise).
+// xin: the residual-stream values x[m][n_i] (RESID only; the caller loads them, early if it can).
 template <int EPI, int NBW>
-SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, const float (&val)[NBW], float inv) {
+SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, const float (&val)[NBW], float inv,
+                           const float (&xin)[NBW]) {
     if constexpr (EPI == EPI_PARTIAL) {
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
@@ -126,7 +138,7 @@ SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, c
         for (int i = 0; i < NBW; ++i) {
             const int n = (g * NBW + i) * 32 + col;
             if (n < a.N) {
-                const float nv = a.x[(size_t)m * a.N + n] + val[i];
+                const float nv = xin[i] + val[i];
                 a.x[(size_t)m * a.N + n] = nv;
                 a.xb[Layout<bf16_t>::a_index(m, n, a.N)] = float_to_bf16(nv);
             }
@@ -142,9 +154,8 @@ SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, c
         const float gt = val[0] * inv, up = val[1] * inv;
         const int n = g * 32 + col;
         if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
-    } else {  // EPI_QKV
-        const QkvRow r = qkv_row(a, m);
-        qkv_store(a, r, g, col, val[0] * inv, val[1] * inv);
+    } else {
+        static_assert(EPI != EPI_QKV, "the QKV epilogue is qkv_row + qkv_rotation + qkv_store, called by the kernels");
     }
 }
 
@@ -181,6 +192,34 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #define SJD_STAMP(i) do { } while (0)
 #endif
     SJD_STAMP(0);
+
+    // What the epilogue will need from memory is requested now, ahead of the weight stream, so that its latency
+    // is not paid after the last MFMA: residual values (RESID), row destination and rotation (QKV).  Thread t ends
+    // up with elements e = t, t + 64 NW, ... of every tile (see the reduction below).
+    constexpr int EPT = 1024 / (NW * 64);  // elements per thread per tile
+    [[maybe_unused]] float xpre[MT][NBW][EPT];
+    [[maybe_unused]] QkvRow qrow[MT][EPT];
+    [[maybe_unused]] float rot_c[MT][EPT], rot_s[MT][EPT];
+    if (EPI == EPI_RESID || EPI == EPI_QKV) {
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int hh = 0; hh < EPT; ++hh) {
+                const int v = wave + NW * hh;
+                const int m = m_base + j * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (EPI == EPI_RESID) {
+#pragma unroll
+                    for (int i = 0; i < NBW; ++i) {
+                        const int n = (g * NBW + i) * 32 + (lane & 31);
+                        xpre[j][i][hh] = m < a.M && n < a.N ? a.x[(size_t)m * a.N + n] : 0.0f;
+                    }
+                } else {
+                    qrow[j][hh].pos = -1;
+                    if (m < a.M) qrow[j][hh] = qkv_row(a, m);
+                    qkv_rotation(a, qrow[j][hh], g, lane & 31, rot_c[j][hh], rot_s[j][hh]);
+                }
+            }
+    }
 
     f32x16 acc[MT][NBW];
 #pragma unroll
@@ -254,7 +293,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             if (lane < 32) ssq_lds[wave][j][lane] = t;
         }
     }
-    constexpr int EPT = 1024 / (NW * 64);  // elements per thread per tile
     float out[MT][NBW][EPT];
 #pragma unroll
     for (int j = 0; j < MT; ++j)
@@ -339,10 +377,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 for (int w = 0; w < NW; ++w) t += ssq_lds[w][j][row];
                 inv = 1.0f / sqrtf(t / (float)(KB * 16) + a.eps);
             }
-            float vals[NBW];
+            float vals[NBW], xin[NBW];
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) vals[i] = out[j][i][hh];
-            skinny_epilogue<EPI, NBW>(a, ks, m, g, col, vals, inv);
+            for (int i = 0; i < NBW; ++i) {
+                vals[i] = out[j][i][hh];
+                xin[i] = EPI == EPI_RESID ? xpre[j][i][hh] : 0.0f;
+            }
+            if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[j][hh], g, col, vals[0] * inv, vals[NBW - 1] * inv, rot_c[j][hh], rot_s[j][hh]);
+            else skinny_epilogue<EPI, NBW>(a, ks, m, g, col, vals, inv, xin);
         }
     SJD_STAMP(3);
 }
@@ -424,8 +466,7 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     return hipGetLastError();
 }
 
-// nw = wavefronts per workgroup: 8 when there are fewer column groups than CUs (one fat workgroup per CU), 4
-// when there are more (two or more resident workgroups per CU overlap one's epilogue with another's streaming).
+// nw = wavefronts per workgroup (4 or 8), the caller's choice.
 template <int EPI>
 inline hipError_t launch_skinny(hipStream_t st, const SkinnyArgs &a, int MT, int groups, int nbw, int nw = 8) {
     return nw == 4 ? launch_skinny_nw<EPI, 4>(st, a, MT, groups, nbw) : launch_skinny_nw<EPI, 8>(st, a, MT, groups, nbw);

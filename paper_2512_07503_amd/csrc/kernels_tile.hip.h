@@ -187,8 +187,22 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
                 float inv = 1.0f;
                 if (kNorm) inv = 1.0f / sqrtf(ssq_lds[wave][j][row] / (float)(KB * 16) + a.eps);
                 const float vals[2] = {park[v * 64], park[(16 + v) * 64]};
-                if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[(wave * 2 + j) * 32 + row], g, col, vals[0] * inv, vals[1] * inv);
-                else skinny_epilogue<EPI, 2>(a, ks, m, g, col, vals, inv);
+                if constexpr (EPI == EPI_QKV) {
+                    const QkvRow &r = qrow[(wave * 2 + j) * 32 + row];
+                    float c, sn;
+                    qkv_rotation(a, r, g, col, c, sn);
+                    qkv_store(a, r, g, col, vals[0] * inv, vals[1] * inv, c, sn);
+                } else {
+                    float xin[2] = {0.0f, 0.0f};
+                    if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            const int n = (g * 2 + i) * 32 + col;
+                            if (n < a.N) xin[i] = a.x[(size_t)m * a.N + n];
+                        }
+                    }
+                    skinny_epilogue<EPI, 2>(a, ks, m, g, col, vals, inv, xin);
+                }
             }
         }
 }

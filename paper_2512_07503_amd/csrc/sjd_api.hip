@@ -333,7 +333,10 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         return a.ksplit == 1 || need <= c->skinny_part_elems;
     };
     auto no_room = [&]() { sjd_set_error(c->err, "split-K workspace too small"); return SJD_EINVAL; };
-    auto nw_for = [](int groups) { return groups >= 150 ? 4 : 8; };
+    // measured (cold weights): from about 50 column groups on, 4 wavefronts with the same ring depth stream a
+    // workgroup's share faster than 8 (the second wavefront of a SIMD only queues behind the first) and halve the
+    // LDS reduction; with fewer groups 8 wavefronts are needed to keep enough loads in flight per CU
+    auto nw_for = [](int groups) { return groups >= 50 ? 4 : 8; };
     // many rows: LDS-staged 256 x 128 tiles (the projections are a dense contraction there, not a weight stream)
     const bool tile = M >= TILE_M && !(md.kernel_flags & SJD_KERNELS_ROWGROUPS);
     // output / down projection: x += A W^T.  One kernel when a workgroup's share is small, else K split over
