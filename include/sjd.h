@@ -21,7 +21,9 @@
  *    pointers are ordinary process memory;
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream);
  *    it is borrowed and must outlive the context; all work of a context is
- *    enqueued on it;
+ *    enqueued on it.  On an ordinary stream sjd_step records its launches once
+ *    (stream capture, thread-local mode) and replays them as a HIP graph; on
+ *    the default stream, which cannot be captured, it launches them one by one;
  *  - a context is not thread-safe; different contexts are independent.
  */
 #ifndef SJD_H
@@ -49,7 +51,8 @@ enum sjd_dtype { SJD_F32 = 0, SJD_BF16 = 1 };
 /* kernel_flags bits */
 enum {
     SJD_KERNELS_REFERENCE = 1, /* use the plain (non-MFMA) GEMM and attention kernels */
-    SJD_NO_GRAPH = 2,          /* never capture the step into a HIP graph             */
+    SJD_NO_GRAPH = 2,          /* never capture the step into a HIP graph: launch its
+                                * kernels one by one                                   */
     SJD_KERNELS_ROWGROUPS = 4, /* bf16, >= 256 rows: keep the 64-row-group streaming projection
                                 * kernels instead of the LDS-staged tile kernels       */
     SJD_ATTENTION_CHUNKED = 8  /* bf16: always split the context over workgroups and merge

@@ -128,7 +128,13 @@ class Decoder:
         sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed, 0)
         self.ctx = C.c_void_p()
         self.L, self.Vs, self.n_seqs = window, arch["sample_hi"] - arch["sample_lo"], 0
-        _check(lib().sjd_create(C.byref(self.md), C.byref(w), C.byref(sp), _stream_ptr(), C.byref(self.ctx)))
+        # The context runs on the caller's current stream, unless that is the default stream: the library can only
+        # capture its step into a HIP graph on an ordinary stream, so it then gets one of its own (default priority).
+        # Either way the weights must be complete before sjd_create reads them.
+        cur = torch.cuda.current_stream()
+        cur.synchronize()
+        self._stream = cur if cur.cuda_stream != 0 else torch.cuda.Stream()
+        _check(lib().sjd_create(C.byref(self.md), C.byref(w), C.byref(sp), C.c_void_p(self._stream.cuda_stream), C.byref(self.ctx)))
 
     def close(self):
         if getattr(self, "ctx", None):

@@ -63,6 +63,12 @@ struct sjd_ctx {
     int hd = 0, Vs = 0, L = 0, S = 0, n_seqs = 0, pt = 0, pps = 0, n_pages = 0, max_visible = 0;
     size_t esize = 0;
     bool prefilled = false, all_done = false;
+    // one sjd_step = the same launch sequence with the same arguments every time (what changes lives in device
+    // memory): captured once per batch size into a HIP graph and replayed
+    bool use_graph = false;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    int graph_n_seqs = 0;
     bool attn_mfma = false;
     int attn_chunk = 0, attn_nchunks = 0;
     bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
@@ -687,6 +693,22 @@ int finish_step(sjd_ctx *c, sjd_step_result *out) {
     return SJD_OK;
 }
 
+// everything one decoding step launches, in stream order (the host reads the verdicts back afterwards)
+int enqueue_step(sjd_ctx *c) {
+    SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
+    int rc = forward_any(c, true);
+    if (rc) return rc;
+    return run_decide(c);
+}
+
+void drop_graph(sjd_ctx *c) {
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+    if (c->graph) (void)hipGraphDestroy(c->graph);
+    c->graph_exec = nullptr;
+    c->graph = nullptr;
+    c->graph_n_seqs = 0;
+}
+
 }  // namespace
 
 // =================================================================================================
@@ -697,6 +719,7 @@ const char *sjd_last_error(const sjd_ctx *ctx) { return ctx ? ctx->err : g_creat
 void sjd_destroy(sjd_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
+    drop_graph(c);
     for (void *p : c->allocations) (void)hipFree(p);
     if (c->res_host) (void)hipHostFree(c->res_host);
     for (hipEvent_t e : c->tracer.pool) (void)hipEventDestroy(e);
@@ -727,6 +750,7 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
     c->sp.top_k = sampling->top_k;
     c->sp.seed = sampling->seed;
     const bool f32 = desc->dtype == SJD_F32;
+    c->use_graph = !(desc->kernel_flags & SJD_NO_GRAPH) && hip_stream != nullptr;  // the default stream cannot be captured
     c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&
                    attention_mfma_supported(c->L, desc->n_heads, desc->n_kv_heads, c->hd, c->pt);
     c->fused = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) && c->hd % 64 == 0 && (c->S * 2 * c->L <= 64 || (2 * c->L) % 64 == 0) &&
@@ -828,10 +852,24 @@ int sjd_step(sjd_ctx *c, sjd_step_result *out) {
     if (!c) return SJD_EINVAL;
     if (!out) { sjd_set_error(c->err, "null result pointer"); return SJD_EINVAL; }
     if (!c->prefilled) { sjd_set_error(c->err, "sjd_step before sjd_prefill"); return SJD_ESTATE; }
-    SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
-    int rc = forward_any(c, true);
-    if (rc) return rc;
-    if ((rc = run_decide(c))) return rc;
+    int rc;
+    if (c->use_graph && !c->tracer.on) {   // per-kernel event timing needs the kernels one by one
+        if (c->graph_exec && c->graph_n_seqs != c->n_seqs) drop_graph(c);
+        if (!c->graph_exec) {
+            SJD_HIP_TRY(c->err, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+            rc = enqueue_step(c);
+            hipGraph_t g = nullptr;
+            const hipError_t e = hipStreamEndCapture(c->stream, &g);  // always end the capture, also after a failed launch
+            if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+            if (e != hipSuccess || !g) { sjd_set_error(c->err, "stream capture of the step failed: %s", hipGetErrorString(e)); return SJD_EDEVICE; }
+            c->graph = g;
+            SJD_HIP_TRY(c->err, hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
+            c->graph_n_seqs = c->n_seqs;
+        }
+        SJD_HIP_TRY(c->err, hipGraphLaunch(c->graph_exec, c->stream));
+    } else if ((rc = enqueue_step(c))) {
+        return rc;
+    }
     return finish_step(c, out);
 }
 

@@ -39,7 +39,9 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
                                         ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
-                                        ("small_tile", 0), ("small_tile", 4), ("small_fused64", 8)])
+                                        ("small_tile", 0), ("small_tile", 4), ("small_fused64", 8),
+                                        # flag 2: kernels launched one by one instead of the replayed HIP graph
+                                        ("small_f32", 2), ("small_fused64", 2), ("small_sub", 2)])
 def test_small_models_step_by_step(oracle, name, flags):
     cfg = workload.get_config(name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, kernel_flags=flags, head_alpha=6.0, std=0.08, random_gains=True)
