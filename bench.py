@@ -198,7 +198,7 @@ def main():
     if dom:
         try:   # HBM bytes per launch measured with rocprofv3 --pmc (profiles/pmc_traffic.json), if this config has them
             pmc = json.load(open(os.path.join(ROOT, "profiles", "pmc_traffic.json"))).get(args.config, {}).get("kernels", {})
-            key = dominant if dominant in pmc else ("gemm_out+gemm_down" if dominant in ("gemm_out", "gemm_down") else None)
+            key = dominant if dominant in pmc else None
             if key:
                 roofline["traffic"] = pmc[key]["fetch_bytes"] + pmc[key]["write_bytes"]
                 roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE scaled by a 256 MiB copy; bytes per launch"
