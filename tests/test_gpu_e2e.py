@@ -54,6 +54,24 @@ def test_small_models_step_by_step(oracle, name, flags):
     print(name, "steps", steps, "worst logits error abs/rel:", worst)
 
 
+@pytest.mark.parametrize("name,window,tau,top_k", [("small_fused64", 1, None, None), ("small_fused64", None, float("inf"), None),
+                                                   ("small_fused64", None, None, 1), ("small_f32", 1, None, None),
+                                                   ("small_f32", None, float("inf"), None), ("small_f32", None, None, 1),
+                                                   ("small_sub", 2, 0.0, None)])
+def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
+    """The comparison modes of Sec. 5 run through the same step: L = 1 is plain autoregressive decoding, tau = inf is
+    SJD without reuse (Eq. 6), K = 1 greedy Jacobi decoding; tau = 0 keeps every draft with nonzero probability."""
+    cfg = workload.get_config(name)
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=window, tau=tau, top_k=top_k, head_alpha=6.0, std=0.08)
+    f32 = cfg["dtype"] == "f32"
+    worst, steps = _lockstep(o, g, cfg["n_seqs"], 400, tol_abs=1e-4 if f32 else None, tol_rel=None if f32 else 8e-2)
+    for s in range(cfg["n_seqs"]):
+        assert len(g.tokens(s)) == n_img[s]
+    if window == 1:
+        assert steps == max(n_img)      # one token per forward
+    print(name, window, tau, top_k, "steps", steps, "worst logits error abs/rel:", worst)
+
+
 def test_cfg0_whole_sequence_identity(oracle):
     """configs[0] in fp32: the GPU decode and the oracle decode, each on its own forward, give the same 256 tokens."""
     cfg = workload.get_config("cfg0")
