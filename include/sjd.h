@@ -55,9 +55,11 @@ enum {
                                 * kernels one by one                                   */
     SJD_KERNELS_ROWGROUPS = 4, /* bf16, >= 256 rows: keep the 64-row-group streaming projection
                                 * kernels instead of the LDS-staged tile kernels       */
-    SJD_ATTENTION_CHUNKED = 8  /* bf16: always split the context over workgroups and merge
+    SJD_ATTENTION_CHUNKED = 8, /* bf16: always split the context over workgroups and merge
                                 * in a second kernel, also where one workgroup per head
                                 * would do (short contexts)                            */
+    SJD_KERNELS_TILES = 16     /* bf16, >= 256 rows: the tile kernels also for models too
+                                * narrow to fill the chip with 256 x 128 tiles         */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

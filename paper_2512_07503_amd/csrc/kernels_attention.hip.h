@@ -97,7 +97,8 @@ __global__ void pack_q_kernel(const T *__restrict__ src, T *__restrict__ dst, in
 
 // ------------------------------------------------------------------------------------ MFMA, bf16
 // Flash-decoding over the paged cache.  A wavefront owns one (segment, query head, chunk of `chunk`
-// tokens) and all L <= 32 queries of the window.  Per block of 32 tokens:
+// tokens, tile of 32 window rows); windows longer than 32 are covered by several query tiles.  Per block of 32
+// tokens:
 //   S^T (tokens x queries) = K (A operand, fragment-major page) x Q^T (B operand)       hd / 16 MFMAs
 //   online softmax per query = per accumulator column: in-lane over 16 values + one cross-half shuffle
 //   O^T (dims x queries)  += V^T (A operand) x P^T (B operand)                            2 hd / 32 MFMAs
@@ -112,22 +113,24 @@ struct AttnArgs {
     const int32_t *row_tok;  // [segments * L]
     const int32_t *seg_kv;   // cached positions per segment
     const int32_t *seg_n;    // active window rows per segment
-    float *part_o;           // [segments * H * n_chunks][32][hd]
-    float *part_ml;          // [segments * H * n_chunks][2][32]  (running max, running sum)
+    float *part_o;           // [segments * H * n_qt * n_chunks][32][hd]
+    float *part_ml;          // [segments * H * n_qt * n_chunks][2][32]  (running max, running sum)
     bf16_t *out_act;         // [M][H * hd] GEMM-operand layout
     float *out_plain;        // optional [M][H][hd]
     int L, H, Hkv, hd, chunk, n_chunks;
+    int n_qt;                // query tiles of 32 window rows = ceil(L / 32)
     float scale_log2e;       // 1 / sqrt(hd) * log2(e)
 };
 
 // One wavefront's pass over the 32-token blocks t_begin, t_begin + t_stride, ... < t_end of (segment seg, query
-// head h): leaves the unnormalised O^T in o, the running maximum (base-2 logits) in m_run and this lane's half of
-// the running sum in l_run; query = lane % 32.
+// head h, query tile qt): leaves the unnormalised O^T in o, the running maximum (base-2 logits) in m_run and this
+// lane's half of the running sum in l_run; window row = 32 qt + lane % 32.
 template <int HD>
-SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int t_begin, int t_end, int t_stride, int kv, int n_tot, int lane,
+SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int qt, int t_begin, int t_end, int t_stride, int kv, int n_tot, int lane,
                           f32x16 (&o)[HD / 32], float &m_run, float &l_run) {
     constexpr int KF = HD / 16, DB = HD / 32;
-    const u32x4 *qp = reinterpret_cast<const u32x4 *>(a.q + ((size_t)seg * a.H + h) * Layout<bf16_t>::q_elems(a.L, HD)) + lane;
+    const u32x4 *qp = reinterpret_cast<const u32x4 *>(a.q + ((size_t)seg * a.H + h) * Layout<bf16_t>::q_elems(a.L, HD)) +
+                      (size_t)qt * KF * 64 + lane;
     u32x4 qf[KF];
 #pragma unroll
     for (int kb = 0; kb < KF; ++kb) qf[kb] = qp[kb * 64];
@@ -151,7 +154,7 @@ SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int t_begi
     m_run = -INFINITY;
     l_run = 0.0f;
     if (t_begin >= t_end) return;
-    const int query = lane & 31;
+    const int query = 32 * qt + (lane & 31);
 
     u32x4 kf[KF], vf[2 * DB];
     {
@@ -228,20 +231,21 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int G = a.H / a.Hkv;
-    const int c = blockIdx.x, kvh = blockIdx.y, seg = blockIdx.z;
+    const int c = blockIdx.x, kvh = blockIdx.y, seg = blockIdx.z / a.n_qt, qt = blockIdx.z % a.n_qt;
     const int h = kvh * G + wave;
     const int n_act = a.seg_n[seg];
     const int kv = a.seg_kv[seg];
     const int n_tot = n_act > 0 ? kv + n_act : 0;
+    const int n_vis = min(n_tot, kv + 32 * (qt + 1));  // nothing later is visible to this query tile
     const int t_begin = c * a.chunk;
-    if (t_begin >= n_tot) return;
-    const int t_end = t_begin + a.chunk < n_tot ? t_begin + a.chunk : n_tot;
+    if (t_begin >= n_vis || 32 * qt >= n_act) return;
+    const int t_end = t_begin + a.chunk < n_vis ? t_begin + a.chunk : n_vis;
     f32x16 o[DB];
     float m_run, l_run;
-    attention_wave<HD>(a, seg, h, kvh, t_begin, t_end, 32, kv, n_tot, lane, o, m_run, l_run);
+    attention_wave<HD>(a, seg, h, kvh, qt, t_begin, t_end, 32, kv, n_tot, lane, o, m_run, l_run);
     const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
-    const size_t slot = ((size_t)seg * a.H + h) * a.n_chunks + c;
+    const size_t slot = (((size_t)seg * a.H + h) * a.n_qt + qt) * a.n_chunks + c;
     float *po = a.part_o + slot * 32 * HD + (size_t)query * HD;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -263,14 +267,15 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
     static_assert(16 % NS == 0, "NS must divide 16");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = blockIdx.x, seg = blockIdx.y;
+    const int h = blockIdx.x, seg = blockIdx.y, qt = blockIdx.z;
     const int kvh = h / (a.H / a.Hkv);
     const int n_act = a.seg_n[seg];
     const int kv = a.seg_kv[seg];
     const int n_tot = n_act > 0 ? kv + n_act : 0;
+    const int n_vis = 32 * qt < n_act ? min(n_tot, kv + 32 * (qt + 1)) : 0;  // nothing later is visible to this query tile
     f32x16 o[DB];
     float m_run, l_run;
-    attention_wave<HD>(a, seg, h, kvh, 32 * wave, n_tot, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
+    attention_wave<HD>(a, seg, h, kvh, qt, 32 * wave, n_vis, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
     const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
 
@@ -289,8 +294,8 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
 #pragma unroll
     for (int w = 0; w < NS; ++w) denom += exp2f(ml[w][0][query] - m_use) * ml[w][1][query];
     const float scale = exp2f(m_run - m_use);  // 0 for a wavefront that saw nothing
-    const int m = seg * a.L + query;
-    const bool row = query < a.L;
+    const int m = seg * a.L + 32 * qt + query;
+    const bool row = 32 * qt + query < a.L;
     const bool active = row && a.row_tok[m] >= 0 && denom > 0.0f;
     const float inv = active ? 1.0f / denom : 0.0f;
 #pragma unroll
@@ -321,17 +326,19 @@ __global__ void attention_combine_kernel(AttnArgs a) {
     const int seg = m / a.L, i_win = m % a.L, hd = a.hd;
     const bool active = a.row_tok[m] >= 0;
     const int n_tot = a.seg_kv[seg] + a.seg_n[seg];
-    const int nc = active ? (n_tot + a.chunk - 1) / a.chunk : 0;
-    const size_t slot0 = ((size_t)seg * a.H + h) * a.n_chunks;
+    const int qt = i_win >> 5, iq = i_win & 31;
+    const int n_vis = min(n_tot, a.seg_kv[seg] + 32 * (qt + 1));  // the chunks this row's query tile went through
+    const int nc = active ? (n_vis + a.chunk - 1) / a.chunk : 0;
+    const size_t slot0 = (((size_t)seg * a.H + h) * a.n_qt + qt) * a.n_chunks;
     float mx = -INFINITY;
-    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, a.part_ml[(slot0 + c) * 64 + i_win]);
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, a.part_ml[(slot0 + c) * 64 + iq]);
     float denom = 0.0f;
-    for (int c = 0; c < nc; ++c) denom += exp2f(a.part_ml[(slot0 + c) * 64 + i_win] - mx) * a.part_ml[(slot0 + c) * 64 + 32 + i_win];
+    for (int c = 0; c < nc; ++c) denom += exp2f(a.part_ml[(slot0 + c) * 64 + iq] - mx) * a.part_ml[(slot0 + c) * 64 + 32 + iq];
     const float inv = nc > 0 ? 1.0f / denom : 0.0f;
     for (int j = threadIdx.x; j < hd; j += blockDim.x) {
         float acc = 0.0f;
         for (int c = 0; c < nc; ++c)
-            acc += exp2f(a.part_ml[(slot0 + c) * 64 + i_win] - mx) * a.part_o[(slot0 + c) * 32 * hd + (size_t)i_win * hd + j];
+            acc += exp2f(a.part_ml[(slot0 + c) * 64 + iq] - mx) * a.part_o[(slot0 + c) * 32 * hd + (size_t)iq * hd + j];
         acc *= inv;
         if (a.out_act) a.out_act[Layout<bf16_t>::a_index(m, h * hd + j, a.H * hd)] = float_to_bf16(acc);
         if (a.out_plain) a.out_plain[((size_t)m * a.H + h) * hd + j] = acc;
@@ -339,7 +346,7 @@ __global__ void attention_combine_kernel(AttnArgs a) {
 }
 
 inline bool attention_mfma_supported(int L, int H, int Hkv, int hd, int page_tokens) {
-    return L <= 32 && (hd == 64 || hd == 128) && H / Hkv <= 4 && page_tokens % 32 == 0;
+    return L >= 1 && (hd == 64 || hd == 128) && H / Hkv <= 4 && page_tokens % 32 == 0;
 }
 
 // One workgroup per (segment, head) pays while the keys and values of a head are a small stream for one CU.
@@ -348,12 +355,12 @@ inline bool attention_onepass_pays(int max_tokens, int hd) { return (size_t)max_
 // n_segments segments of L rows each.  onepass: contexts short enough for one workgroup per (segment, head).
 inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n_segments, bool onepass = false) {
     if (onepass) {
-        const dim3 grid(a.H, n_segments);
+        const dim3 grid(a.H, n_segments, a.n_qt);
         if (a.hd == 64) attention_onepass_kernel<64, 8><<<grid, 512, 0, st>>>(a);
         else attention_onepass_kernel<128, 8><<<grid, 512, 0, st>>>(a);
         return hipGetLastError();
     }
-    dim3 grid(a.n_chunks, a.Hkv, n_segments);
+    dim3 grid(a.n_chunks, a.Hkv, n_segments * a.n_qt);
     const int G = a.H / a.Hkv;
     if (a.hd == 64) attention_mfma_kernel<64><<<grid, G * 64, 0, st>>>(a);
     else attention_mfma_kernel<128><<<grid, G * 64, 0, st>>>(a);

@@ -231,6 +231,7 @@ template <> int run_attention<bf16_t>(sjd_ctx *c, const KvPool &pool, int M) {
     a.L = c->L; a.H = c->md.n_heads; a.Hkv = c->md.n_kv_heads; a.hd = c->hd;
     a.chunk = c->attn_chunk;
     a.n_chunks = c->attn_nchunks;
+    a.n_qt = ceil_div(c->L, 32);
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)c->hd));
     SJD_LAUNCH(c, KC_ATTENTION, launch_attention_mfma(c->stream, a, M / c->L, c->attn_onepass));
     return SJD_OK;
@@ -344,7 +345,10 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     // LDS reduction; with fewer groups 8 wavefronts are needed to keep enough loads in flight per CU
     auto nw_for = [](int groups) { return groups >= 50 ? 4 : 8; };
     // many rows: LDS-staged 256 x 128 tiles (the projections are a dense contraction there, not a weight stream)
-    const bool tile = M >= TILE_M && !(md.kernel_flags & SJD_KERNELS_ROWGROUPS);
+    // ... provided the model is wide enough for 256 x 128 tiles to fill the chip (QKV: >= 96 tiles); a narrow model
+    // with a long window keeps the row-group kernels, which give it more workgroups
+    const bool tile = M >= TILE_M && !(md.kernel_flags & SJD_KERNELS_ROWGROUPS) &&
+                      ((md.kernel_flags & SJD_KERNELS_TILES) || ceil_div((H + 2 * Hkv) * (hd / 64) * 2, 4) * ceil_div(M, TILE_M) >= 96);
     // output / down projection: x += A W^T.  One kernel when a workgroup's share is small, else K split over
     // grid.y with the partial sums added by resid_reduce_kernel after the kernel boundary.
     auto resid = [&](int cls, const void *A, const void *W, int K) -> int {
@@ -577,13 +581,13 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
     }
     if (c->attn_mfma) {
         // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
-        long want = (long)md.max_ctx * S * 2 * H / 1500;
+        long want = (long)md.max_ctx * S * 2 * H * ceil_div(L, 32) / 1500;
         int chunk = (int)((want + 63) / 64) * 64;
         if (chunk < 128) chunk = 128;
         c->attn_chunk = chunk;
         c->attn_onepass = !(md.kernel_flags & SJD_ATTENTION_CHUNKED) && attention_onepass_pays(md.max_ctx, hd);
         c->attn_nchunks = ceil_div(md.max_ctx, chunk);
-        const size_t slots = (size_t)S * 2 * H * c->attn_nchunks;
+        const size_t slots = (size_t)S * 2 * H * ceil_div(L, 32) * c->attn_nchunks;
         if ((rc = dev_alloc(c, &c->part_o, slots * 32 * hd * sizeof(float)))) return rc;
         if ((rc = dev_alloc(c, &c->part_ml, slots * 64 * sizeof(float)))) return rc;
     }

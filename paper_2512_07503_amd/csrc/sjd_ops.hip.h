@@ -101,8 +101,9 @@ int op_attention(hipStream_t st, int flags, const void *q, const void *k, const 
         int32_t *seg_n;
         a.chunk = 128;
         a.n_chunks = ceil_div(n_tok, a.chunk);
-        if (!s.alloc(&a.part_o, (size_t)H * a.n_chunks * 32 * hd * sizeof(float), st) ||
-            !s.alloc(&a.part_ml, (size_t)H * a.n_chunks * 64 * sizeof(float), st) || !s.alloc(&seg_n, 4, st)) {
+        a.n_qt = ceil_div(n, 32);
+        if (!s.alloc(&a.part_o, (size_t)H * a.n_qt * a.n_chunks * 32 * hd * sizeof(float), st) ||
+            !s.alloc(&a.part_ml, (size_t)H * a.n_qt * a.n_chunks * 64 * sizeof(float), st) || !s.alloc(&seg_n, 4, st)) {
             sjd_set_error(g_create_error, "allocation failed");
             return SJD_ENOMEM;
         }

@@ -39,7 +39,7 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
                                         ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
-                                        ("small_tile", 0), ("small_tile", 4), ("small_fused64", 8),
+                                        ("small_tile", 16), ("small_tile", 0), ("small_fused64", 8),
                                         # flag 2: kernels launched one by one instead of the replayed HIP graph
                                         ("small_f32", 2), ("small_fused64", 2), ("small_sub", 2)])
 def test_small_models_step_by_step(oracle, name, flags):
@@ -57,7 +57,11 @@ def test_small_models_step_by_step(oracle, name, flags):
 @pytest.mark.parametrize("name,window,tau,top_k", [("small_fused64", 1, None, None), ("small_fused64", None, float("inf"), None),
                                                    ("small_fused64", None, None, 1), ("small_f32", 1, None, None),
                                                    ("small_f32", None, float("inf"), None), ("small_f32", None, None, 1),
-                                                   ("small_sub", 2, 0.0, None)])
+                                                   ("small_sub", 2, 0.0, None),
+                                                   # windows longer than one 32-row attention tile: 48 (generic GEMMs),
+                                                   # 64 (two row groups of the fused projections)
+                                                   ("small_fused64", 48, None, None), ("small_fused64", 64, None, None),
+                                                   ("small_fused128", 96, None, None)])
 def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
     """The comparison modes of Sec. 5 run through the same step: L = 1 is plain autoregressive decoding, tau = inf is
     SJD without reuse (Eq. 6), K = 1 greedy Jacobi decoding; tau = 0 keeps every draft with nonzero probability."""

@@ -118,6 +118,9 @@ def test_window_attention_fp32(sjd, n, ctx, H, Hkv, hd):
                                                    # one workgroup per head at the full LlamaGen-shaped context; the same
                                                    # small cases through the chunk + merge kernels (flag 8)
                                                    (16, 690, 20, 20, 64, 0), (16, 690, 20, 20, 64, 8), (16, 119, 20, 20, 64, 8),
-                                                   (32, 300, 8, 2, 128, 8), (1, 77, 4, 4, 64, 8), (16, 0, 2, 2, 64, 8)])
+                                                   (32, 300, 8, 2, 128, 8), (1, 77, 4, 4, 64, 8), (16, 0, 2, 2, 64, 8),
+                                                   # windows longer than one 32-row query tile (paper-sized windows)
+                                                   (96, 200, 4, 4, 64, 0), (96, 200, 4, 4, 64, 8), (250, 300, 4, 2, 128, 0),
+                                                   (250, 300, 4, 2, 128, 8), (40, 0, 2, 2, 64, 0), (33, 31, 2, 1, 128, 8)])
 def test_window_attention_bf16(sjd, n, ctx, H, Hkv, hd, flags):
     _attention_case(sjd, n, ctx, H, Hkv, hd, "bf16", flags=flags)

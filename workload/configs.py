@@ -49,8 +49,8 @@ TINY = {
     # shapes that take the fused small-M bf16 path (head_dim 64 / 128, M = 32 / 64)
     "small_fused64": _cfg(_arch(2, 256, 4, 2, 512, 2048), "bf16", 13, 60, 16, 100, 15),
     "small_fused128": _cfg(_arch(3, 256, 2, 1, 352, 1500, 20, 1460), "bf16", 70, 90, 32, 200, 16),
-    # 5 sequences x 2 x window 32 = 320 rows: the many-row projection kernels, with a ragged last row tile and
-    # ragged last column tiles (d = 192, F = 352, 1440 sampled ids)
+    # 5 sequences x 2 x window 32 = 320 rows: the many-row projection kernels (tile kernels when forced by flag, else
+    # row groups), with a ragged last row tile and ragged last column tiles (d = 192, F = 352, 1440 sampled ids)
     "small_tile": _cfg(_arch(2, 192, 3, 1, 352, 1500, 20, 1460), "bf16", 20, 70, 32, 150, 17, n_seqs=5),
     "small_sub": _cfg(_arch(2, 64, 2, 1, 96, 700, 100, 612), "f32", 7, 30, 5, 40, 14, n_seqs=3),
 }
