@@ -25,6 +25,16 @@
  *     window drawn from that row;
  *   - near the end of the image the window shrinks to the tokens remaining.
  *
+ * Sec. 4.2 (initialisation with a spatial prior) changes only how a slot that
+ * has never had a draft is filled (init_mode of the sampling parameters):
+ *   (a) copy of the token to its left, (b) copy of the token one image row
+ *   above, (c) a draw from the distribution the left neighbour was drawn from.
+ * A copied draft was "drawn" from the one-hot distribution at that token, so
+ * that is its reference; a draft of (c) has the row it was drawn from.  Slots
+ * of the very first window (no image token exists yet) and slots of (b) in
+ * the first image row are filled uniformly.  (d), the distribution of the
+ * token above, would need the rows of a whole image row kept; not built.
+ *
  * Randomness: Philox4x32-10, key = seed, counter = (step, row, sequence, 0).
  * Word 0 is the acceptance uniform of the draft verified at that row, words
  * 1-2 the 64-bit uniform of the one draw made at that row, word 3 a fresh
@@ -40,6 +50,7 @@
 #endif
 
 enum { OK = 0, EINVAL_ = -1, ENOMEM_ = -2, ESTATE_ = -3, ECAPACITY_ = -5 };
+enum { REF_UNIFORM = -1, REF_ONEHOT = -2 };
 
 typedef struct {
     int32_t cond_len, uncond_len, n_image;
@@ -47,7 +58,7 @@ typedef struct {
     int32_t *out;  /* [n_image] */
     int32_t anchor[2];
     int32_t *tok;     /* [L] window tokens, slot 0 unused (anchor above) */
-    int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform */
+    int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform, -2 = one-hot at the draft */
     float *ref_e;     /* [L][V_s] rows of the previous step */
     uint64_t *ref_Z;  /* [L] */
     oracle_cache *cache[2];
@@ -91,6 +102,7 @@ int oracle_create(const oracle_model_desc *md, const oracle_weights *w, const or
     if (md->d_model % md->n_heads || md->n_heads % md->n_kv_heads || (md->d_model / md->n_heads) % 2) return EINVAL_;
     if (md->sample_lo < 0 || md->sample_hi > md->vocab || md->sample_hi <= md->sample_lo) return EINVAL_;
     if (sp->top_k < 1 || !(sp->temperature > 0.0f)) return EINVAL_;
+    if (sp->init_mode < 0 || sp->init_mode > 3 || (sp->init_mode == 2 && sp->row_width < 1)) return EINVAL_;
     oracle_ctx *c = (oracle_ctx *)calloc(1, sizeof *c);
     if (!c) return ENOMEM_;
     c->md = *md; c->w = *w; c->sp = *sp;
@@ -178,6 +190,7 @@ int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids
 
 /* probability weight of token id `tok` under reference of slot k */
 static void ref_of(const oracle_ctx *c, const seq_state *q, int k, int32_t tok, uint64_t *w, uint64_t *Z) {
+    if (q->ref_row[k] == REF_ONEHOT) { *w = 1; *Z = 1; return; } /* tok is the copied token itself */
     if (q->ref_row[k] < 0) { *w = 1; *Z = (uint64_t)c->Vs; return; }
     const float *row = q->ref_e + (size_t)q->ref_row[k] * c->Vs;
     *w = oracle_weight_of(row[tok - c->md.sample_lo]);
@@ -213,7 +226,8 @@ static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
     if (rejected) {
         int rr = q->ref_row[a + 1];
         const float *qe = rr < 0 ? NULL : q->ref_e + (size_t)rr * Vs;
-        y = lo + oracle_draw_residual(pa, c->new_Z[a], qe, rr < 0 ? 0 : q->ref_Z[rr], Vs, u64);
+        if (rr == REF_ONEHOT) y = lo + oracle_draw_residual_onehot(pa, c->new_Z[a], q->tok[a + 1] - lo, Vs, u64);
+        else y = lo + oracle_draw_residual(pa, c->new_Z[a], qe, rr < 0 ? 0 : q->ref_Z[rr], Vs, u64);
     } else {
         y = lo + oracle_draw(pa, c->new_Z[a], Vs, u64);
     }
@@ -262,9 +276,24 @@ static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
                                         ((uint64_t)r[1] << 32) | r[2]);
             ref2[k2] = Le - 1;
         } else {
+            /* a slot that never had a draft (Sec. 4.2); image index of its token: n_img + k2 - 1 */
+            const int mode = c->sp.init_mode, up = q->n_img + k2 - 1 - c->sp.row_width;
             philox(c, step, (uint32_t)k, (uint32_t)s, r);
-            tok2[k2] = fresh_token(c, r[3]);
-            ref2[k2] = -1;
+            if (mode == 1) {
+                tok2[k2] = k2 == 1 ? y : tok2[k2 - 1];
+                ref2[k2] = REF_ONEHOT;
+            } else if (mode == 2 && c->sp.row_width >= 1 && up >= 0) {
+                tok2[k2] = up < q->n_img ? q->out[up] : tok2[up - q->n_img + 1];
+                ref2[k2] = REF_ONEHOT;
+            } else if (mode == 3) {
+                /* its left neighbour (or that one's, ...) was drawn from the last row of this step */
+                tok2[k2] = lo + oracle_draw(c->new_e + (size_t)(Le - 1) * Vs, c->new_Z[Le - 1], Vs,
+                                            ((uint64_t)r[1] << 32) | r[2]);
+                ref2[k2] = Le - 1;
+            } else {
+                tok2[k2] = fresh_token(c, r[3]);
+                ref2[k2] = REF_UNIFORM;
+            }
         }
     }
     q->anchor[0] = q->anchor[1] = y;

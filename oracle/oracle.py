@@ -32,7 +32,7 @@ class Weights(C.Structure):
 
 class Sampling(C.Structure):
     _fields_ = [("cfg_scale", C.c_float), ("temperature", C.c_float), ("top_k", C.c_int32),
-                ("reuse_tau", C.c_float), ("seed", C.c_uint64)]
+                ("reuse_tau", C.c_float), ("seed", C.c_uint64), ("init_mode", C.c_int32), ("row_width", C.c_int32)]
 
 
 class StepResult(C.Structure):
@@ -221,12 +221,12 @@ def forward_window_logits(arch, weights, prefix, window):
 
 
 def decode_trials(arch, weights, window, cond, uncond, n_image, n_trials, seed0=0, cfg_scale=3.0,
-                  temperature=1.0, top_k=8, reuse_tau=float("inf")):
+                  temperature=1.0, top_k=8, reuse_tau=float("inf"), init_mode=0, row_width=0):
     """Histogram of decoded sequences over n_trials seeds (see oracle_decode_trials)."""
     c = np.ascontiguousarray(cond, dtype=np.int32)
     u = np.ascontiguousarray(uncond, dtype=np.int32)
     m = _Model(arch, weights, window, max(len(c), len(u)) + n_image)
-    sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, 0)
+    sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, 0, init_mode, row_width)
     counts = np.zeros(m.Vs ** n_image, dtype=np.int64)
     steps = C.c_int64(0)
     rc = lib().oracle_decode_trials(C.byref(m.md), C.byref(m.w), C.byref(sp), _ip(c), len(c), _ip(u), len(u),
@@ -240,11 +240,11 @@ class Oracle:
     """The oracle decoder: create -> prefill -> step* (same call shape as the GPU library)."""
 
     def __init__(self, arch, weights, window, max_ctx, cfg_scale=3.0, temperature=1.0, top_k=2000,
-                 reuse_tau=0.5, seed=0, max_seqs=1):
+                 reuse_tau=0.5, seed=0, max_seqs=1, init_mode=0, row_width=0):
         self.model = _Model(arch, weights, window, max_ctx)
         self.L = window
         self.Vs = self.model.Vs
-        self.sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed)
+        self.sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed, init_mode, row_width)
         self.ctx = C.c_void_p()
         rc = lib().oracle_create(C.byref(self.model.md), C.byref(self.model.w), C.byref(self.sp), max_seqs,
                                  C.byref(self.ctx))

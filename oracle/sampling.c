@@ -153,6 +153,21 @@ int32_t oracle_draw_residual(const float *e_p, uint64_t Z_p, const float *e_q, u
     return V - 1;
 }
 
+/* Eq. 3 against a one-hot reference q = delta_x (a draft that was copied, not drawn): max(0, p - q) is p with the
+ * entry of x removed; if nothing else has weight fall back to p. */
+int32_t oracle_draw_residual_onehot(const float *e_p, uint64_t Z_p, int32_t x, int32_t V, uint64_t u64) {
+    uint64_t R = 0;
+    for (int32_t v = 0; v < V; ++v) R += residual_weight(prob(oracle_weight_of(e_p[v]), Z_p), v == x ? 1.0 : 0.0);
+    if (R == 0) return oracle_draw(e_p, Z_p, V, u64);
+    uint64_t target = mulhi64(u64, R);
+    uint64_t prefix = 0;
+    for (int32_t v = 0; v < V; ++v) {
+        prefix += residual_weight(prob(oracle_weight_of(e_p[v]), Z_p), v == x ? 1.0 : 0.0);
+        if (prefix > target) return v;
+    }
+    return V - 1;
+}
+
 void oracle_law_trials(const float *e_p, uint64_t Z_p, const float *e_q, uint64_t Z_q, int32_t V,
                        uint64_t seed, int64_t n_trials, int64_t *counts, int64_t *n_rejected) {
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};

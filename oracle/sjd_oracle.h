@@ -58,6 +58,11 @@ typedef struct {
     int32_t top_k;
     float reuse_tau; /* 0.5 = SJD++ (Sec. 5.1); +INF = SJD without reuse */
     uint64_t seed;
+    /* Sec. 4.2, how a window slot that has never had a draft is filled:
+     *   0 uniformly over the sampled ids; 1 copy of the token to its left (a); 2 copy of the token one image row
+     *   above, row_width tokens back (b); 3 drawn from the distribution its left neighbour was drawn from (c). */
+    int32_t init_mode;
+    int32_t row_width; /* tokens per image row, mode 2 only */
 } oracle_sampling;
 
 typedef struct {
@@ -84,6 +89,8 @@ int32_t oracle_draw(const float *e_p, uint64_t Z_p, int32_t V, uint64_t u64);
 /* q_e == NULL means the uniform reference (w = 1, Z = V). */
 int32_t oracle_draw_residual(const float *e_p, uint64_t Z_p, const float *e_q, uint64_t Z_q, int32_t V,
                              uint64_t u64);
+/* the same against a one-hot reference at x (a copied draft) */
+int32_t oracle_draw_residual_onehot(const float *e_p, uint64_t Z_p, int32_t x, int32_t V, uint64_t u64);
 
 /* Statistical helper for the Theorem-1 pins: n_trials times, draw x ~ q with
  * the integer inverse CDF, test acceptance against p, on rejection draw from

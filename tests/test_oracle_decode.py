@@ -83,30 +83,28 @@ def test_top_1_is_greedy_decoding(oracle, L, tau, seed):
         u.append(int(got[i]))
 
 
-def test_no_reuse_decoding_has_the_autoregressive_joint_law(oracle):
-    """Theorem 1 end to end: with tau = +inf (Eq. 6) the decoded sequence is distributed exactly as ancestral
-    sampling.  Toy model, V = 8, N = 3, window 3: the AR joint is enumerated over all 512 sequences."""
-    cfg, arch, w, cond, uncond = _model("toy", alpha=0.6, std=0.3)
-    V, N, s, K = 8, 3, 3.0, 6
+def _ar_joint(oracle, arch, w, cond, uncond, V, N, s, K):
     joint = np.zeros(V ** N)
+    memo = {}
     for idx in range(V ** N):
         seq = [(idx // V ** i) % V for i in range(N)]
-        c, u, pr = list(cond[0]), list(uncond[0]), 1.0
-        for tok in seq:
-            lc = oracle.forward_logits(arch, w, c)[-1]
-            lu = oracle.forward_logits(arch, w, u)[-1]
-            e, Z = oracle.sampling_row(lc, lu, s, 1.0, K)
+        pr = 1.0
+        for i, tok in enumerate(seq):
+            key = tuple(seq[:i])
+            if key not in memo:
+                lc = oracle.forward_logits(arch, w, list(cond) + list(key))[-1]
+                lu = oracle.forward_logits(arch, w, list(uncond) + list(key))[-1]
+                memo[key] = oracle.sampling_row(lc, lu, s, 1.0, K)
+            e, Z = memo[key]
             pr *= oracle.weight_of(float(e[tok])) / Z
-            c.append(tok)
-            u.append(tok)
         joint[idx] = pr
     assert abs(joint.sum() - 1.0) < 1e-9
-    n = 400_000
-    counts, steps = oracle.decode_trials(arch, w, 3, cond[0], uncond[0], N, n, seed0=1000, cfg_scale=s, top_k=K,
-                                         reuse_tau=float("inf"))
+    return joint
+
+
+def _chi_square_against(joint, counts, n, min_cells):
     assert counts.sum() == n
     assert counts[joint == 0].sum() == 0
-    assert 1.0 <= N / (steps / n) <= 3.0
     # pool cells with small expectation so that the chi-square approximation holds
     order = np.argsort(joint)
     exp, obs, acc_e, acc_o = [], [], 0.0, 0
@@ -119,8 +117,87 @@ def test_no_reuse_decoding_has_the_autoregressive_joint_law(oracle):
             exp.append(acc_e); obs.append(acc_o); acc_e, acc_o = 0.0, 0
     if acc_e > 0:
         exp[-1] += acc_e; obs[-1] += acc_o
-    assert len(exp) > 30
+    assert len(exp) > min_cells
     assert stats.chisquare(obs, exp).pvalue > 0.01
+
+
+def test_no_reuse_decoding_has_the_autoregressive_joint_law(oracle):
+    """Theorem 1 end to end: with tau = +inf (Eq. 6) the decoded sequence is distributed exactly as ancestral
+    sampling.  Toy model, V = 8, N = 3, window 3: the AR joint is enumerated over all 512 sequences."""
+    cfg, arch, w, cond, uncond = _model("toy", alpha=0.6, std=0.3)
+    V, N, s, K = 8, 3, 3.0, 6
+    joint = _ar_joint(oracle, arch, w, cond[0], uncond[0], V, N, s, K)
+    n = 400_000
+    counts, steps = oracle.decode_trials(arch, w, 3, cond[0], uncond[0], N, n, seed0=1000, cfg_scale=s, top_k=K,
+                                         reuse_tau=float("inf"))
+    assert 1.0 <= N / (steps / n) <= 3.0
+    _chi_square_against(joint, counts, n, 30)
+
+
+@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 2), (3, 0)])
+def test_spatial_initialisation_keeps_the_autoregressive_joint_law(oracle, mode, row_width):
+    """Sec. 4.2: however a new slot is initialised (copy of the left or upper neighbour with a one-hot reference, a
+    draw from the neighbour's row with that row as reference), verification against the true proposal keeps the
+    output law exact (Theorem 1 holds for any q).  Window 2 on 4 tokens, so new slots do get initialised (after
+    every fully accepted window); a wrong reference for them would bend the joint."""
+    cfg, arch, w, cond, uncond = _model("toy", alpha=0.6, std=0.3)
+    V, N, s, K = 8, 4, 3.0, 6
+    joint = _ar_joint(oracle, arch, w, cond[0], uncond[0], V, N, s, K)
+    n = 150_000
+    counts, steps = oracle.decode_trials(arch, w, 2, cond[0], uncond[0], N, n, seed0=5000 + mode, cfg_scale=s, top_k=K,
+                                         reuse_tau=float("inf"), init_mode=mode, row_width=row_width)
+    assert 1.0 <= N / (steps / n) <= 2.0
+    _chi_square_against(joint, counts, n, 40)
+
+
+@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 3), (3, 0)])
+def test_spatial_initialisation_fills_new_slots_as_stated(oracle, mode, row_width):
+    """New slots of the window after a step: (a) equal the token to their left, (b) equal the token row_width places
+    back in the image (uniform in the first image row), both with the one-hot reference; (c) are the inverse-CDF
+    draws from the last row of the step with that row as reference.  Slots of the first window are uniform."""
+    cfg, arch, w, cond, uncond = _model("small_f32")
+    L, Vs, lo, N, K = 6, arch["sample_hi"] - arch["sample_lo"], arch["sample_lo"], 40, 60
+    P = cfg["prompt_len"]
+    seen = 0
+    for seed in range(6):
+        dec = oracle.Oracle(arch, w, L, P + N, top_k=K, reuse_tau=0.5, seed=seed, init_mode=mode, row_width=row_width)
+        assert dec.prefill(cond[:1], uncond[:1], [N]) == 0
+        toks, refs, n_slots = dec.window()
+        for k in range(1, n_slots):   # first window: uniform whatever the mode
+            words = oracle.philox([0, k, 0, 0], [seed, 0])
+            assert toks[k] == lo + ((words[3] * Vs) >> 32) and refs[k] == -1
+        step = 0
+        while True:
+            step += 1
+            Le = dec.window()[2]
+            logits = dec.peek_logits()
+            res = dec.step()[0]
+            if res["done"]:
+                break
+            a = res["n_accepted"]
+            after, refs, Le2 = dec.window()
+            final = dec.tokens()
+            n_img = len(final)
+            for k2 in range(1, Le2):
+                k = k2 + a + 1
+                if k <= Le:
+                    continue                      # carried, refreshed or drawn from the last row: other tests
+                seen += 1
+                idx = n_img + k2 - 1              # image index of this slot's token
+                if mode == 1:
+                    assert after[k2] == (final[-1] if k2 == 1 else after[k2 - 1]) and refs[k2] == -2
+                elif mode == 2:
+                    up = idx - row_width
+                    if up >= 0:
+                        assert after[k2] == (final[up] if up < n_img else after[up - n_img + 1]) and refs[k2] == -2
+                    else:
+                        words = oracle.philox([step, k, 0, 0], [seed, 0])
+                        assert after[k2] == lo + ((words[3] * Vs) >> 32) and refs[k2] == -1
+                else:
+                    e, Z = oracle.sampling_row(logits[0, 0, Le - 1], logits[0, 1, Le - 1], 3.0, 1.0, K)
+                    words = oracle.philox([step, k, 0, 0], [seed, 0])
+                    assert after[k2] == lo + oracle.draw(e, Z, (words[1] << 32) | words[2]) and refs[k2] == Le - 1
+    assert seen > 20
 
 
 def test_equal_distributions_accept_the_whole_window(oracle):
