@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--window", type=int, default=0, help="override the configuration's Jacobi window L (1 = plain autoregressive decoding)")
     ap.add_argument("--tau", type=float, default=None, help="override the reuse threshold (inf = SJD without token reuse, Eq. 6)")
     ap.add_argument("--top-k", type=int, default=0, help="override top-K (1 = greedy Jacobi decoding)")
+    ap.add_argument("--init-mode", type=int, default=0,
+                    help="initialisation of new window slots: 0 uniform, 1 repeat left, 2 repeat above, 3 resample from the left row")
+    ap.add_argument("--row-width", type=int, default=0, help="tokens per image row for --init-mode 2 (default: sqrt of the image tokens)")
     ap.add_argument("--no-finish-image", action="store_true", help="do not run the image to its end for forwards/image")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
@@ -97,7 +100,8 @@ def main():
     cond, uncond = workload.make_prompts(arch, cfg["seed"], S, P)
     dec = sjd.Decoder(arch, weights, cfg["dtype"], L, P + N, max_seqs=S, cfg_scale=cfg["cfg_scale"],
                       temperature=cfg["temperature"], top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"],
-                      kernel_flags=args.kernel_flags)
+                      kernel_flags=args.kernel_flags, init_mode=args.init_mode,
+                      row_width=args.row_width or int(round(N ** 0.5)))
     host_weights = None
     if not args.no_cpu_baseline:
         host_weights = {k: ([t.float().cpu().numpy() for t in v] if isinstance(v, list) else v.float().cpu().numpy())

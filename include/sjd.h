@@ -108,7 +108,16 @@ typedef struct {
     int32_t top_k;
     float reuse_tau;  /* 0.5 in the paper; +INF disables reuse (Eq. 6) */
     uint64_t seed;
-    int32_t init_mode; /* 0 = new drafts drawn uniformly over the sampled ids (the only mode) */
+    /* Sec. 4.2, how a window slot that has never had a draft is filled (slots of the first window, before any image
+     * token exists, are always uniform):
+     *   0  drawn uniformly over the sampled ids (reference: uniform);
+     *   1  copy of the token to its left (reference: one-hot at that token);
+     *   2  copy of the token one image row above, row_width tokens back (one-hot; uniform in the first row);
+     *   3  drawn from the distribution its left neighbour was drawn from, i.e. the last row of the step
+     *      (reference: that row).
+     * The fourth strategy of the paper (the distribution of the token above) is not built. */
+    int32_t init_mode;
+    int32_t row_width; /* tokens per image row; used by init_mode 2 (>= 1 there) */
 } sjd_sampling;
 
 typedef struct {

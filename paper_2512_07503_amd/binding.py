@@ -36,7 +36,7 @@ class Weights(C.Structure):
 
 class Sampling(C.Structure):
     _fields_ = [("cfg_scale", C.c_float), ("temperature", C.c_float), ("top_k", C.c_int32), ("reuse_tau", C.c_float),
-                ("seed", C.c_uint64), ("init_mode", C.c_int32)]
+                ("seed", C.c_uint64), ("init_mode", C.c_int32), ("row_width", C.c_int32)]
 
 
 class StepResult(C.Structure):
@@ -106,7 +106,7 @@ class Decoder:
     lm_head and per-layer lists attn_norm, wq, wk, wv, wo, mlp_norm, w_gate, w_up, w_down."""
 
     def __init__(self, arch, weights, dtype, window, max_ctx, max_seqs=1, cfg_scale=3.0, temperature=1.0, top_k=2000,
-                 reuse_tau=0.5, seed=0, kv_page_tokens=0, kernel_flags=0):
+                 reuse_tau=0.5, seed=0, kv_page_tokens=0, kernel_flags=0, init_mode=0, row_width=0):
         import torch
         want = torch.float32 if dtype == "f32" else torch.bfloat16
         tensors = [weights[n] for n in ("tok_emb", "final_norm", "lm_head")] + [t for n in _PER_LAYER for t in weights[n]]
@@ -125,7 +125,7 @@ class Decoder:
             arr = (C.c_void_p * arch["n_layers"])(*[t.data_ptr() for t in weights[n]])
             keep.append(arr)
             setattr(w, n, C.cast(arr, _VPP))
-        sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed, 0)
+        sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed, init_mode, row_width)
         self.ctx = C.c_void_p()
         self.L, self.Vs, self.n_seqs = window, arch["sample_hi"] - arch["sample_lo"], 0
         # The context runs on the caller's current stream, unless that is the default stream: the library can only

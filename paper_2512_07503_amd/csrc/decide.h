@@ -15,7 +15,7 @@ struct DecideState {
     int32_t max_img;   // capacity of out_tok per sequence
     int32_t *win_tok;  // [S][L]   window tokens (slot 0 unused)
     int32_t *anchor;   // [S][2]   first window input of the cond / uncond branch
-    int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform
+    int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform, -2 = one-hot at the draft
     int32_t *n_img;    // [S]      image tokens final so far
     int32_t *n_image;  // [S]      image tokens wanted
     int32_t *kv_len;   // [S][2]   committed cache positions per branch
@@ -23,6 +23,7 @@ struct DecideState {
     int32_t *out_tok;  // [S][max_img]
     int32_t *acc_len;  // [S]      accepted drafts of the current step
     int32_t *cand;     // [S][L]   per output row: the token drawn (or kept) there this step
+    int32_t *cand_new; // [S][L]   per slot of the NEXT window: the draw for a slot that never had a draft (init_mode 3)
     uint32_t *step;    // [1]      step counter (0 after prefill)
     float *e_buf[2];   // [S][L][V] softmax weights, ping-pong by step parity
     uint64_t *Z_buf[2];// [S][L]
@@ -33,6 +34,7 @@ struct SamplingParams {
     float cfg_scale, inv_temperature, tau;
     int32_t top_k;
     uint64_t seed;
+    int32_t init_mode, row_width;  // Sec. 4.2 initialisation of new slots (see sjd_sampling)
 };
 
 // Rows of the forward: token and position per GEMM row, cache length and active rows per segment

@@ -357,6 +357,8 @@ __global__ void stage_prompt_kernel(RowMap rm, const int32_t *prompt, const int3
     if (k == 0) { rm.seg_kv[seg] = start; rm.seg_n[seg] = n; }
 }
 
+constexpr int kRefUniform = -1, kRefOneHot = -2;  // values of ref_row below 0
+
 // ------------------------------------------------------------------- a11: verification (Eq. 2)
 // One block per sequence; every draft is tested in parallel, the first rejection is found with a
 // wavefront ballot per 64 drafts and a minimum across wavefronts.
@@ -380,9 +382,9 @@ __global__ void verify_kernel(DecideState d, uint64_t seed) {
             draw_words(seed, step, (uint32_t)(k - 1), (uint32_t)s, w);
             const int x = d.win_tok[s * L + k] - d.lo;
             const uint64_t wp = weight_of(e_new[(long)(k - 1) * V + x]);
-            const int rr = d.ref_row[s * L + k];
+            const int rr = d.ref_row[s * L + k];  // -1 uniform: 1 / V;  -2 one-hot at this very token: 1 / 1
             const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
-            const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+            const uint64_t Zq = rr == kRefOneHot ? 1ull : (rr < 0 ? (uint64_t)V : Z_ref[rr]);
             rejected = !accept_rule(w[0], wp, Z_new[k - 1], wq, Zq);
         }
         const uint64_t mask = __ballot(rejected);
@@ -460,12 +462,24 @@ SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20
 //                     rejected draft, or a plain draw from row a when every draft was accepted;
 //   a < k <= Le - 2   slot k + 1: kept if p > tau q (Eq. 4-5) else redrawn from row k;
 //   k == Le - 1 > a   no draft was predicted by this row: its slot is drawn from it.
-__global__ void draw_kernel(DecideState d, uint64_t seed, float tau) {
-    const int r = blockIdx.x, L = d.L, V = d.V, s = r / L, k = r % L;
+// With init_mode 3 the grid has 2 L blocks per sequence: block kk >= Le is the new slot with old index kk + 1 (it has
+// no row of its own) and draws from the last row Le - 1 with its own counter, if the next window has that slot.
+__global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_per_seq) {
+    const int r = blockIdx.x, L = d.L, V = d.V, s = r / rows_per_seq;
+    int k = r % rows_per_seq;
     const int Le = d.Le[s];
-    if (k >= Le) return;
+    if (Le == 0) return;
     const int a = d.acc_len[s];
-    if (k < a) return;
+    int new_slot = -1;  // index in the next window of the never-drafted slot this block draws for
+    if (k >= Le) {
+        if (rows_per_seq == L) return;  // no draws for new slots in the other modes
+        const int remaining = d.n_image[s] - (d.n_img[s] + a + 1);
+        const int Le2 = remaining < L ? remaining : L;
+        new_slot = k + 1 - a - 1;
+        if (new_slot >= Le2) return;
+    } else if (k < a) {
+        return;
+    }
     const uint32_t step = *d.step;
     const float *e_new = d.e_buf[step & 1u] + (long)s * L * V;
     const float *e_ref = d.e_buf[(step & 1u) ^ 1u] + (long)s * L * V;
@@ -474,20 +488,27 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau) {
     extern __shared__ uint64_t sums[];
 
     uint32_t w[4];
-    draw_words(seed, step, (uint32_t)k, (uint32_t)s, w);
+    draw_words(seed, step, (uint32_t)(new_slot >= 0 ? k + 1 : k), (uint32_t)s, w);
     const uint64_t u64 = ((uint64_t)w[1] << 32) | w[2];
+    if (new_slot >= 0) k = Le - 1;
     const float *pk = e_new + (long)k * V;
     const uint64_t Zp = Z_new[k];
     auto from_p = [&](int v) { return weight_of(pk[v]); };
+    if (new_slot >= 0) {
+        const int t = block_inverse_cdf(from_p, V, u64, sums);
+        if (threadIdx.x == 0) d.cand_new[s * L + new_slot] = d.lo + t;
+        return;
+    }
 
     int tok;
     if (k == a && a < Le - 1) {
         const int rr = d.ref_row[s * L + a + 1];
         const float *qrow = rr < 0 ? nullptr : e_ref + (long)rr * V;
         const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+        const int x = d.win_tok[s * L + a + 1] - d.lo;
         auto resid = [&](int v) {
             double P = prob(weight_of(pk[v]), Zp);
-            double Q = prob(qrow ? weight_of(qrow[v]) : 1ull, Zq);
+            double Q = rr == kRefOneHot ? (v == x ? 1.0 : 0.0) : prob(qrow ? weight_of(qrow[v]) : 1ull, Zq);
             return residual_weight(P, Q);
         };
         tok = block_inverse_cdf(resid, V, u64, sums);
@@ -496,7 +517,7 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau) {
         const int x = d.win_tok[s * L + k + 1] - d.lo;
         const int rr = d.ref_row[s * L + k + 1];
         const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
-        const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+        const uint64_t Zq = rr == kRefOneHot ? 1ull : (rr < 0 ? (uint64_t)V : Z_ref[rr]);
         if (keep_rule(tau, weight_of(pk[x]), Zp, wq, Zq)) {
             tok = x;
         } else {
@@ -509,7 +530,7 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau) {
 }
 
 // ----------------------------------------------- a14: finalise, shift the window, refill, commit
-__global__ void commit_kernel(DecideState d, uint64_t seed) {
+__global__ void commit_kernel(DecideState d, uint64_t seed, int init_mode, int row_width) {
     const int s = blockIdx.x, L = d.L;
     const int Le = d.Le[s];
     sjd_step_result *res = d.res + s;
@@ -533,10 +554,41 @@ __global__ void commit_kernel(DecideState d, uint64_t seed) {
             if (k <= Le) {           // slot k of this step (k == Le: the slot predicted by the last row)
                 tok = d.cand[s * L + k - 1];
                 ref = k - 1;
-            } else {                 // a slot that never had a row: fresh uniform draft
-                uint32_t w[4];
-                draw_words(seed, step, (uint32_t)k, (uint32_t)s, w);
-                tok = d.lo + (int)__umulhi(w[3], (uint32_t)d.V);
+            } else {                 // a slot that never had a draft (Sec. 4.2)
+                const int n_new = n_img + a + 1;  // image tokens final after this step; this slot's token is n_new + k2 - 1
+                auto uniform_of = [&](int kk) {   // the uniform draft of old slot index kk
+                    uint32_t w[4];
+                    draw_words(seed, step, (uint32_t)kk, (uint32_t)s, w);
+                    return d.lo + (int)__umulhi(w[3], (uint32_t)d.V);
+                };
+                if (init_mode == 1) {
+                    // every new slot repeats its left neighbour, so all of them equal the last slot that has a row
+                    // (k == Le, present only after a rejection) or else the token that just became final
+                    tok = a < Le - 1 ? d.cand[s * L + Le - 1] : y;
+                    ref = kRefOneHot;
+                } else if (init_mode == 2) {
+                    // the token row_width places back; that place may itself be a new slot of this window, filled
+                    // by the same rule: follow the chain
+                    int j = k2;
+                    for (;;) {
+                        const int up = n_new + j - 1 - row_width;
+                        if (up < 0) {                       // first image row: slot j is uniform (and k2 copies it)
+                            tok = uniform_of(j + a + 1);
+                            ref = j == k2 ? kRefUniform : kRefOneHot;
+                            break;
+                        }
+                        ref = kRefOneHot;
+                        if (up < n_img + a) { tok = out[up]; break; }   // final before this step, or accepted in it (copied above)
+                        if (up == n_new - 1) { tok = y; break; }
+                        j = up - n_new + 1;                 // slot j of the next window
+                        if (j + a + 1 <= Le) { tok = d.cand[s * L + j + a]; break; }       // a slot that has a row
+                    }
+                } else if (init_mode == 3) {
+                    tok = d.cand_new[s * L + k2];
+                    ref = Le - 1;
+                } else {
+                    tok = uniform_of(k);
+                }
             }
         }
         d.win_tok[s * L + k2] = tok;
@@ -629,12 +681,13 @@ hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingPar
 }
 
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    draw_kernel<<<n_seqs * d.L, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau);
+    const int rows_per_seq = sp.init_mode == 3 ? 2 * d.L : d.L;
+    draw_kernel<<<n_seqs * rows_per_seq, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq);
     return hipGetLastError();
 }
 
 hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    commit_kernel<<<n_seqs, 64, 0, st>>>(d, sp.seed);
+    commit_kernel<<<n_seqs, 64, 0, st>>>(d, sp.seed, sp.init_mode, sp.row_width);
     return hipGetLastError();
 }
 

@@ -613,6 +613,7 @@ int alloc_state(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &d.out_tok, (size_t)S * d.max_img * 4))) return rc;
     if ((rc = dev_alloc(c, &d.acc_len, (size_t)S * 4))) return rc;
     if ((rc = dev_alloc(c, &d.cand, (size_t)S * L * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.cand_new, (size_t)S * L * 4))) return rc;
     if ((rc = dev_alloc(c, &d.step, 4))) return rc;
     for (int b = 0; b < 2; ++b) {
         if ((rc = dev_alloc(c, &d.e_buf[b], (size_t)S * L * c->Vs * sizeof(float)))) return rc;
@@ -665,8 +666,9 @@ int validate_desc(const sjd_model_desc *md, const sjd_weights *w, const sjd_samp
         sjd_set_error(err, "bf16 needs head_dim %% 32 == 0, d_model %% 16 == 0, d_ff %% 16 == 0"); return SJD_EINVAL;
     }
     if (!(md->rms_eps > 0.0f) || !(md->rope_theta > 0.0f)) { sjd_set_error(err, "bad rms_eps / rope_theta"); return SJD_EINVAL; }
-    if (sp->top_k < 1 || !(sp->temperature > 0.0f) || sp->init_mode != 0 || sp->reuse_tau != sp->reuse_tau || sp->reuse_tau < 0.0f) {
-        sjd_set_error(err, "bad sampling parameters (top_k >= 1, temperature > 0, tau >= 0, init_mode 0)"); return SJD_EINVAL;
+    if (sp->top_k < 1 || !(sp->temperature > 0.0f) || sp->init_mode < 0 || sp->init_mode > 3 ||
+        (sp->init_mode == 2 && sp->row_width < 1) || sp->reuse_tau != sp->reuse_tau || sp->reuse_tau < 0.0f) {
+        sjd_set_error(err, "bad sampling parameters (top_k >= 1, temperature > 0, tau >= 0, init_mode 0..3, row_width >= 1 for init_mode 2)"); return SJD_EINVAL;
     }
     if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm ||
         !w->w_gate || !w->w_up || !w->w_down) {
@@ -753,6 +755,8 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
     c->sp.tau = sampling->reuse_tau;
     c->sp.top_k = sampling->top_k;
     c->sp.seed = sampling->seed;
+    c->sp.init_mode = sampling->init_mode;
+    c->sp.row_width = sampling->row_width;
     const bool f32 = desc->dtype == SJD_F32;
     c->use_graph = !(desc->kernel_flags & SJD_NO_GRAPH) && hip_stream != nullptr;  // the default stream cannot be captured
     c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&

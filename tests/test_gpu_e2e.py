@@ -76,6 +76,23 @@ def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
     print(name, window, tau, top_k, "steps", steps, "worst logits error abs/rel:", worst)
 
 
+@pytest.mark.parametrize("name,mode,row_width,tau", [("small_f32", 1, 0, None), ("small_f32", 2, 3, None), ("small_f32", 2, 12, None),
+                                                     ("small_f32", 3, 0, None), ("small_sub", 1, 0, float("inf")),
+                                                     ("small_sub", 2, 2, None), ("small_sub", 3, 0, 0.0),
+                                                     ("small_fused64", 1, 0, None), ("small_fused64", 2, 5, None),
+                                                     ("small_fused64", 3, 0, None)])
+def test_spatial_initialisation_step_by_step(oracle, name, mode, row_width, tau):
+    """Sec. 4.2: new window slots copied from the left / upper neighbour (one-hot reference) or drawn from the
+    neighbour's row; tokens AND references of every window must equal the oracle's at every step."""
+    cfg = workload.get_config(name)
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, tau=tau, head_alpha=6.0, std=0.08, init_mode=mode, row_width=row_width)
+    f32 = cfg["dtype"] == "f32"
+    worst, steps = _lockstep(o, g, cfg["n_seqs"], 400, tol_abs=1e-4 if f32 else None, tol_rel=None if f32 else 8e-2)
+    for s in range(cfg["n_seqs"]):
+        assert len(g.tokens(s)) == n_img[s]
+    print(name, mode, row_width, tau, "steps", steps)
+
+
 def test_cfg0_whole_sequence_identity(oracle):
     """configs[0] in fp32: the GPU decode and the oracle decode, each on its own forward, give the same 256 tokens."""
     cfg = workload.get_config("cfg0")
