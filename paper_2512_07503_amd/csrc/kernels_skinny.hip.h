@@ -46,10 +46,9 @@ struct SkinnyArgs {
     int F;
     // HEAD
     float *logits;
-    // K split across workgroups (grid.y = ksplit > 1): per-workgroup partial tiles and arrival counters
+    // PARTIAL: K split across workgroups (grid.y = ksplit), plain partial sums; the other epilogues run with ksplit 1
     int ksplit, kb_per_split;
-    float *part;             // [groups][ksplit][MT * NBW * 1024 + MT * 32]
-    unsigned int *counters;  // [groups], zero between launches
+    float *part;             // [ksplit][M][N]
 #ifdef SJD_PHASE_TIMING
     unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
 #endif
@@ -312,54 +311,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             }
         }
 
-    // ---- K split across workgroups: every workgroup publishes its partial tile; the one that arrives last
-    //      (whichever it is) adds all of them in the fixed order 0 .. ksplit - 1, so the result does not depend
-    //      on arrival order, and carries on to the epilogue.
-    if (EPI != EPI_PARTIAL && a.ksplit > 1) {
-        constexpr int REC = MT * NBW * 1024 + MT * 32;
-        float *rec = a.part + ((size_t)g * a.ksplit + ks) * REC;
-#pragma unroll
-        for (int j = 0; j < MT; ++j)
-#pragma unroll
-            for (int i = 0; i < NBW; ++i)
-#pragma unroll
-                for (int hh = 0; hh < EPT; ++hh) rec[(j * NBW + i) * 1024 + tid + NW * 64 * hh] = out[j][i][hh];
-        if (kNorm && tid < MT * 32) {
-            float t = 0.0f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) t += ssq_lds[w][tid >> 5][tid & 31];
-            rec[MT * NBW * 1024 + tid] = t;
-        }
-        __shared__ int s_last;
-        __threadfence();  // release: the partial tile is visible device-wide before the arrival is counted
-        __syncthreads();
-        if (tid == 0) s_last = atomicAdd(&a.counters[g], 1u) == (unsigned)a.ksplit - 1u;
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();  // acquire: the other workgroups' tiles
-        const float *all = a.part + (size_t)g * a.ksplit * REC;
-#pragma unroll
-        for (int j = 0; j < MT; ++j)
-#pragma unroll
-            for (int i = 0; i < NBW; ++i)
-#pragma unroll
-                for (int hh = 0; hh < EPT; ++hh) {
-                    float t = 0.0f;
-                    for (int k2 = 0; k2 < a.ksplit; ++k2) t += all[(size_t)k2 * REC + (j * NBW + i) * 1024 + tid + NW * 64 * hh];
-                    out[j][i][hh] = t;
-                }
-        if (kNorm) {
-            if (tid < MT * 32) {
-                float t = 0.0f;
-                for (int k2 = 0; k2 < a.ksplit; ++k2) t += all[(size_t)k2 * REC + MT * NBW * 1024 + tid];
-                ssq_lds[0][tid >> 5][tid & 31] = t;
-#pragma unroll
-                for (int w = 1; w < NW; ++w) ssq_lds[w][tid >> 5][tid & 31] = 0.0f;
-            }
-            __syncthreads();
-        }
-        if (tid == 0) a.counters[g] = 0u;  // ready for the next launch
-    }
     SJD_STAMP(2);
     const int col = lane & 31;
 #pragma unroll

@@ -74,7 +74,6 @@ struct sjd_ctx {
     bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
     float *part_o = nullptr, *part_ml = nullptr;
     float *skinny_part = nullptr;          // partial tiles of K-split fused projections
-    unsigned int *skinny_counters = nullptr;
     size_t skinny_part_elems = 0;
     bool fused = false;  // small-M path: fused projection kernels, RMSNorm gains folded into the weights
     // weights (owned)
@@ -291,17 +290,6 @@ template <typename T> int forward(sjd_ctx *c, bool with_head) {
     return SJD_OK;
 }
 
-// How many workgroups share the K range of one column group.  A workgroup moves (cols + M) * K / ksplit
-// operand elements through its CU's L1; the grid runs in ceil(groups * ksplit / 256) rounds over the 256 CUs.
-// Pick the split with the least rounds x bytes, charging a split for its fix-up (~ the bytes of 2 us).
-int choose_ksplit(int groups, int cols, int M, int KB) {
-    // The in-kernel fix-up needs device-scope release/acquire fences, which on this multi-XCD part write back and
-    // invalidate the whole L2: measured 60-100 us per launch.  It stays switched off; K is split across workgroups
-    // only through a kernel boundary (EPI_PARTIAL + resid_reduce_kernel).
-    (void)groups; (void)cols; (void)M; (void)KB;
-    return 1;
-}
-
 // Small-M bf16 path: five kernels per layer (QKV+RoPE+KV write, attention, out+residual, gate/up+SwiGLU,
 // down+residual); c->xn holds the bf16 copy of the residual stream.
 int forward_fused(sjd_ctx *c, bool with_head) {
@@ -331,14 +319,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     a.logits = c->logits;
     const int nbw_d = ceil_div(d, 32) >= 128 ? 2 : 1;
     a.part = c->skinny_part;
-    a.counters = c->skinny_counters;
-    auto split = [&](int groups, int nbw) {
-        a.ksplit = choose_ksplit(groups, nbw * 32, MT * 32, a.KB);
-        a.kb_per_split = ceil_div(a.KB, a.ksplit);
-        a.ksplit = ceil_div(a.KB, a.kb_per_split);
-        const size_t need = (size_t)groups * a.ksplit * (MT * nbw * 1024 + MT * 32);
-        return a.ksplit == 1 || need <= c->skinny_part_elems;
-    };
+    auto whole_k = [&]() { a.ksplit = 1; a.kb_per_split = a.KB; };
     auto no_room = [&]() { sjd_set_error(c->err, "split-K workspace too small"); return SJD_EINVAL; };
     // measured (cold weights): from about 50 column groups on, 4 wavefronts with the same ring depth stream a
     // workgroup's share faster than 8 (the second wavefront of a SIMD only queues behind the first) and halve the
@@ -379,7 +360,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             while (ks > 1 && a.KB / ks < 32) --ks;
         }
         if (ks == 1) {
-            a.ksplit = 1; a.kb_per_split = a.KB;
+            whole_k();
             SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
             return SJD_OK;
         }
@@ -404,20 +385,20 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.pool = pool;
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wqkv; a.KB = d / 16;
         if (tile) {
-            a.ksplit = 1; a.kb_per_split = a.KB;
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2));
         } else {
-            if (!split((H + 2 * Hkv) * (hd / 64), 2)) return no_room();
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2, nw_for((H + 2 * Hkv) * (hd / 64))));
         }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
         { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd); if (rc) return rc; }
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
         if (tile) {
-            a.ksplit = 1; a.kb_per_split = a.KB;
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2));
         } else {
-            if (!split(F / 32, 2)) return no_room();
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
         }
         { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F); if (rc) return rc; }
@@ -425,10 +406,10 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
         if (tile) {
-            a.ksplit = 1; a.kb_per_split = a.KB;
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2));
         } else {
-            if (!split(ceil_div(ceil_div(c->Vs, 32), 2), 2)) return no_room();
+            whole_k();
             SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
         }
     }
@@ -577,7 +558,6 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         const int widest = std::max(std::max((H + 2 * Hkv) * (hd / 64), F / 32), ceil_div(c->Vs, 64));
         c->skinny_part_elems = std::max((size_t)widest * 8 * (2 * 2 * 1024 + 64), (size_t)8 * M * d);
         if ((rc = dev_alloc(c, &c->skinny_part, c->skinny_part_elems * sizeof(float)))) return rc;
-        if ((rc = dev_alloc(c, &c->skinny_counters, (size_t)(widest + ceil_div(d, 32)) * sizeof(unsigned int)))) return rc;
     }
     if (c->attn_mfma) {
         // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
