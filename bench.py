@@ -62,8 +62,8 @@ def main():
     ap.add_argument("--tau", type=float, default=None, help="override the reuse threshold (inf = SJD without token reuse, Eq. 6)")
     ap.add_argument("--top-k", type=int, default=0, help="override top-K (1 = greedy Jacobi decoding)")
     ap.add_argument("--init-mode", type=int, default=0,
-                    help="initialisation of new window slots: 0 uniform, 1 repeat left, 2 repeat above, 3 resample from the left row")
-    ap.add_argument("--row-width", type=int, default=0, help="tokens per image row for --init-mode 2 (default: sqrt of the image tokens)")
+                    help="initialisation of new window slots: 0 uniform, 1 repeat left, 2 repeat above, 3 / 4 resample from the distribution of the left / upper neighbour")
+    ap.add_argument("--row-width", type=int, default=0, help="tokens per image row for --init-mode 2 and 4 (default: sqrt of the image tokens)")
     ap.add_argument("--no-finish-image", action="store_true", help="do not run the image to its end for forwards/image")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 byte counters)")

@@ -114,10 +114,12 @@ typedef struct {
      *   1  copy of the token to its left (reference: one-hot at that token);
      *   2  copy of the token one image row above, row_width tokens back (one-hot; uniform in the first row);
      *   3  drawn from the distribution its left neighbour was drawn from, i.e. the last row of the step
-     *      (reference: that row).
-     * The fourth strategy of the paper (the distribution of the token above) is not built. */
+     *      (reference: that row);
+     *   4  drawn from the distribution of the token one image row above: the row under which that token became
+     *      final (the context keeps the last row_width of them per sequence), or the reference of the draft at
+     *      that place if it is still in the window (reference: the same; uniform in the first image row). */
     int32_t init_mode;
-    int32_t row_width; /* tokens per image row; used by init_mode 2 (>= 1 there) */
+    int32_t row_width; /* tokens per image row; used by init_mode 2 and 4 (>= 1 there) */
 } sjd_sampling;
 
 typedef struct {

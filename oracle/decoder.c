@@ -32,8 +32,10 @@
  * A copied draft was "drawn" from the one-hot distribution at that token, so
  * that is its reference; a draft of (c) has the row it was drawn from.  Slots
  * of the very first window (no image token exists yet) and slots of (b) in
- * the first image row are filled uniformly.  (d), the distribution of the
- * token above, would need the rows of a whole image row kept; not built.
+ * the first image row are filled uniformly.  (d) draws from the distribution
+ * of the token one image row above: for a token that is final, the row under
+ * which it became final (the last row_width of them are kept per sequence);
+ * for one that is still a draft in the window, that draft's own reference.
  *
  * Randomness: Philox4x32-10, key = seed, counter = (step, row, sequence, 0).
  * Word 0 is the acceptance uniform of the draft verified at that row, words
@@ -50,7 +52,7 @@
 #endif
 
 enum { OK = 0, EINVAL_ = -1, ENOMEM_ = -2, ESTATE_ = -3, ECAPACITY_ = -5 };
-enum { REF_UNIFORM = -1, REF_ONEHOT = -2 };
+enum { REF_UNIFORM = -1, REF_ONEHOT = -2, REF_HIST0 = -3 };
 
 typedef struct {
     int32_t cond_len, uncond_len, n_image;
@@ -58,7 +60,10 @@ typedef struct {
     int32_t *out;  /* [n_image] */
     int32_t anchor[2];
     int32_t *tok;     /* [L] window tokens, slot 0 unused (anchor above) */
-    int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform, -2 = one-hot at the draft */
+    int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform, -2 = one-hot at the draft,
+                       * <= -3: row -3 - ref of `hist_e` */
+    float *hist_e;    /* [row_width][V_s] mode 4: row under which image token i became final, at i % row_width */
+    uint64_t *hist_Z; /* [row_width] */
     float *ref_e;     /* [L][V_s] rows of the previous step */
     uint64_t *ref_Z;  /* [L] */
     oracle_cache *cache[2];
@@ -89,7 +94,7 @@ int oracle_set_num_threads(int32_t n) {
 }
 
 static void seq_release(seq_state *s) {
-    free(s->out); free(s->tok); free(s->ref_row); free(s->ref_e); free(s->ref_Z);
+    free(s->out); free(s->tok); free(s->ref_row); free(s->ref_e); free(s->ref_Z); free(s->hist_e); free(s->hist_Z);
     oracle_cache_free(s->cache[0]);
     oracle_cache_free(s->cache[1]);
     memset(s, 0, sizeof *s);
@@ -102,7 +107,7 @@ int oracle_create(const oracle_model_desc *md, const oracle_weights *w, const or
     if (md->d_model % md->n_heads || md->n_heads % md->n_kv_heads || (md->d_model / md->n_heads) % 2) return EINVAL_;
     if (md->sample_lo < 0 || md->sample_hi > md->vocab || md->sample_hi <= md->sample_lo) return EINVAL_;
     if (sp->top_k < 1 || !(sp->temperature > 0.0f)) return EINVAL_;
-    if (sp->init_mode < 0 || sp->init_mode > 3 || (sp->init_mode == 2 && sp->row_width < 1)) return EINVAL_;
+    if (sp->init_mode < 0 || sp->init_mode > 4 || ((sp->init_mode == 2 || sp->init_mode == 4) && sp->row_width < 1)) return EINVAL_;
     oracle_ctx *c = (oracle_ctx *)calloc(1, sizeof *c);
     if (!c) return ENOMEM_;
     c->md = *md; c->w = *w; c->sp = *sp;
@@ -161,6 +166,11 @@ int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids
         q->ref_row = (int32_t *)calloc((size_t)c->L, sizeof(int32_t));
         q->ref_e = (float *)calloc((size_t)c->L * c->Vs, sizeof(float));
         q->ref_Z = (uint64_t *)calloc((size_t)c->L, sizeof(uint64_t));
+        if (c->sp.init_mode == 4) {
+            q->hist_e = (float *)calloc((size_t)c->sp.row_width * c->Vs, sizeof(float));
+            q->hist_Z = (uint64_t *)calloc((size_t)c->sp.row_width, sizeof(uint64_t));
+            if (!q->hist_e || !q->hist_Z) return ENOMEM_;
+        }
         q->cache[0] = oracle_cache_new(&c->md);
         q->cache[1] = oracle_cache_new(&c->md);
         if (!q->out || !q->tok || !q->ref_row || !q->ref_e || !q->ref_Z || !q->cache[0] || !q->cache[1]) return ENOMEM_;
@@ -191,6 +201,12 @@ int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids
 /* probability weight of token id `tok` under reference of slot k */
 static void ref_of(const oracle_ctx *c, const seq_state *q, int k, int32_t tok, uint64_t *w, uint64_t *Z) {
     if (q->ref_row[k] == REF_ONEHOT) { *w = 1; *Z = 1; return; } /* tok is the copied token itself */
+    if (q->ref_row[k] <= REF_HIST0) {
+        const int h = REF_HIST0 - q->ref_row[k];
+        *w = oracle_weight_of(q->hist_e[(size_t)h * c->Vs + (tok - c->md.sample_lo)]);
+        *Z = q->hist_Z[h];
+        return;
+    }
     if (q->ref_row[k] < 0) { *w = 1; *Z = (uint64_t)c->Vs; return; }
     const float *row = q->ref_e + (size_t)q->ref_row[k] * c->Vs;
     *w = oracle_weight_of(row[tok - c->md.sample_lo]);
@@ -226,14 +242,22 @@ static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
     if (rejected) {
         int rr = q->ref_row[a + 1];
         const float *qe = rr < 0 ? NULL : q->ref_e + (size_t)rr * Vs;
+        uint64_t qZ = rr < 0 ? 0 : q->ref_Z[rr];
+        if (rr <= REF_HIST0) { qe = q->hist_e + (size_t)(REF_HIST0 - rr) * Vs; qZ = q->hist_Z[REF_HIST0 - rr]; }
         if (rr == REF_ONEHOT) y = lo + oracle_draw_residual_onehot(pa, c->new_Z[a], q->tok[a + 1] - lo, Vs, u64);
-        else y = lo + oracle_draw_residual(pa, c->new_Z[a], qe, rr < 0 ? 0 : q->ref_Z[rr], Vs, u64);
+        else y = lo + oracle_draw_residual(pa, c->new_Z[a], qe, qZ, Vs, u64);
     } else {
         y = lo + oracle_draw(pa, c->new_Z[a], Vs, u64);
     }
 
     for (int k = 1; k <= a; ++k) q->out[q->n_img + k - 1] = q->tok[k];
     q->out[q->n_img + a] = y;
+    if (c->sp.init_mode == 4) /* image token n_img + i became final under row i of this step */
+        for (int i = 0; i <= a; ++i) {
+            const int h = (q->n_img + i) % c->sp.row_width;
+            memcpy(q->hist_e + (size_t)h * Vs, c->new_e + (size_t)i * Vs, sizeof(float) * (size_t)Vs);
+            q->hist_Z[h] = c->new_Z[i];
+        }
     q->n_img += a + 1;
     q->cache[0]->len += a + 1;
     q->cache[1]->len += a + 1;
@@ -285,6 +309,15 @@ static void decide(oracle_ctx *c, int s, int Le, oracle_step_result *res) {
             } else if (mode == 2 && c->sp.row_width >= 1 && up >= 0) {
                 tok2[k2] = up < q->n_img ? q->out[up] : tok2[up - q->n_img + 1];
                 ref2[k2] = REF_ONEHOT;
+            } else if (mode == 4 && up >= 0) {
+                /* the distribution of the token one image row above: final -> the kept row; still a draft of this
+                 * window -> whatever that slot's reference is (a row of this step, a kept row, or uniform) */
+                const int ref = up < q->n_img ? REF_HIST0 - up % c->sp.row_width : ref2[up - q->n_img + 1];
+                const uint64_t u = ((uint64_t)r[1] << 32) | r[2];
+                if (ref == REF_UNIFORM) tok2[k2] = fresh_token(c, r[3]);
+                else if (ref >= 0) tok2[k2] = lo + oracle_draw(c->new_e + (size_t)ref * Vs, c->new_Z[ref], Vs, u);
+                else tok2[k2] = lo + oracle_draw(q->hist_e + (size_t)(REF_HIST0 - ref) * Vs, q->hist_Z[REF_HIST0 - ref], Vs, u);
+                ref2[k2] = ref;
             } else if (mode == 3) {
                 /* its left neighbour (or that one's, ...) was drawn from the last row of this step */
                 tok2[k2] = lo + oracle_draw(c->new_e + (size_t)(Le - 1) * Vs, c->new_Z[Le - 1], Vs,

@@ -60,9 +60,10 @@ typedef struct {
     uint64_t seed;
     /* Sec. 4.2, how a window slot that has never had a draft is filled:
      *   0 uniformly over the sampled ids; 1 copy of the token to its left (a); 2 copy of the token one image row
-     *   above, row_width tokens back (b); 3 drawn from the distribution its left neighbour was drawn from (c). */
+     *   above, row_width tokens back (b); 3 drawn from the distribution its left neighbour was drawn from (c);
+     *   4 drawn from the distribution of the token one image row above (d). */
     int32_t init_mode;
-    int32_t row_width; /* tokens per image row, mode 2 only */
+    int32_t row_width; /* tokens per image row, modes 2 and 4 */
 } oracle_sampling;
 
 typedef struct {

@@ -15,7 +15,8 @@ struct DecideState {
     int32_t max_img;   // capacity of out_tok per sequence
     int32_t *win_tok;  // [S][L]   window tokens (slot 0 unused)
     int32_t *anchor;   // [S][2]   first window input of the cond / uncond branch
-    int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform, -2 = one-hot at the draft
+    int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform, -2 = one-hot at the draft,
+                       //          <= -3: row -3 - ref of hist_e
     int32_t *n_img;    // [S]      image tokens final so far
     int32_t *n_image;  // [S]      image tokens wanted
     int32_t *kv_len;   // [S][2]   committed cache positions per branch
@@ -27,6 +28,8 @@ struct DecideState {
     uint32_t *step;    // [1]      step counter (0 after prefill)
     float *e_buf[2];   // [S][L][V] softmax weights, ping-pong by step parity
     uint64_t *Z_buf[2];// [S][L]
+    float *hist_e;     // [S][row_width][V]  init_mode 4: the row under which image token i became final, at i % row_width
+    uint64_t *hist_Z;  // [S][row_width]
     sjd_step_result *res; // [S]
 };
 
@@ -58,6 +61,8 @@ hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const Sampli
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
+// init_mode 4 only, between launch_draw and launch_commit: keeps the rows under which this step's tokens became final
+hipError_t launch_keep_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 
 // stand-alone forms for kernel tests
 hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,

@@ -357,12 +357,25 @@ __global__ void stage_prompt_kernel(RowMap rm, const int32_t *prompt, const int3
     if (k == 0) { rm.seg_kv[seg] = start; rm.seg_n[seg] = n; }
 }
 
-constexpr int kRefUniform = -1, kRefOneHot = -2;  // values of ref_row below 0
+constexpr int kRefUniform = -1, kRefOneHot = -2, kRefHist0 = -3;  // values of ref_row below 0 (<= -3: kept row -3 - ref)
+
+// Row and normaliser a reference code points at (nullptr: uniform or one-hot, which have no row)
+SJD_D const float *ref_row_ptr(const DecideState &d, int s, int rr, const float *e_ref, const uint64_t *Z_ref, int row_width,
+                               uint64_t &Z) {
+    if (rr >= 0) { Z = Z_ref[rr]; return e_ref + (long)rr * d.V; }
+    if (rr <= kRefHist0) {
+        const int h = kRefHist0 - rr;
+        Z = d.hist_Z[s * row_width + h];
+        return d.hist_e + ((long)s * row_width + h) * d.V;
+    }
+    Z = rr == kRefOneHot ? 1ull : (uint64_t)d.V;
+    return nullptr;
+}
 
 // ------------------------------------------------------------------- a11: verification (Eq. 2)
 // One block per sequence; every draft is tested in parallel, the first rejection is found with a
 // wavefront ballot per 64 drafts and a minimum across wavefronts.
-__global__ void verify_kernel(DecideState d, uint64_t seed) {
+__global__ void verify_kernel(DecideState d, uint64_t seed, int row_width) {
     const int s = blockIdx.x, L = d.L, V = d.V;
     const int Le = d.Le[s];
     if (Le == 0) return;
@@ -383,8 +396,9 @@ __global__ void verify_kernel(DecideState d, uint64_t seed) {
             const int x = d.win_tok[s * L + k] - d.lo;
             const uint64_t wp = weight_of(e_new[(long)(k - 1) * V + x]);
             const int rr = d.ref_row[s * L + k];  // -1 uniform: 1 / V;  -2 one-hot at this very token: 1 / 1
-            const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
-            const uint64_t Zq = rr == kRefOneHot ? 1ull : (rr < 0 ? (uint64_t)V : Z_ref[rr]);
+            uint64_t Zq;
+            const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
+            const uint64_t wq = qrow ? weight_of(qrow[x]) : 1ull;
             rejected = !accept_rule(w[0], wp, Z_new[k - 1], wq, Zq);
         }
         const uint64_t mask = __ballot(rejected);
@@ -464,7 +478,25 @@ SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20
 //   k == Le - 1 > a   no draft was predicted by this row: its slot is drawn from it.
 // With init_mode 3 the grid has 2 L blocks per sequence: block kk >= Le is the new slot with old index kk + 1 (it has
 // no row of its own) and draws from the last row Le - 1 with its own counter, if the next window has that slot.
-__global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_per_seq) {
+// Where a new slot of init_mode 4 takes its distribution from: the token row_width places back.  Returns a reference
+// code as stored in ref_row for the NEXT window (>= 0 row of this step, -1 uniform, <= -3 kept row) and, in *src_new,
+// the row of THIS step to draw from when that token becomes final in this very step (its kept row is written later).
+SJD_D int above_source(int k2, int n_img, int a, int Le, int row_width, int *src_new) {
+    const int n_new = n_img + a + 1;
+    *src_new = -1;
+    for (int j = k2;;) {
+        const int up = n_new + j - 1 - row_width;
+        if (up < 0) return kRefUniform;
+        if (up < n_new) {
+            if (up >= n_img) *src_new = up - n_img;
+            return kRefHist0 - up % row_width;
+        }
+        j = up - n_new + 1;                      // the place above is slot j of the next window
+        if (j + a + 1 <= Le) return j + a;       // it has a row of this step: its reference
+    }
+}
+
+__global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_per_seq, int init_mode, int row_width) {
     const int r = blockIdx.x, L = d.L, V = d.V, s = r / rows_per_seq;
     int k = r % rows_per_seq;
     const int Le = d.Le[s];
@@ -490,21 +522,32 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
     uint32_t w[4];
     draw_words(seed, step, (uint32_t)(new_slot >= 0 ? k + 1 : k), (uint32_t)s, w);
     const uint64_t u64 = ((uint64_t)w[1] << 32) | w[2];
-    if (new_slot >= 0) k = Le - 1;
-    const float *pk = e_new + (long)k * V;
-    const uint64_t Zp = Z_new[k];
-    auto from_p = [&](int v) { return weight_of(pk[v]); };
     if (new_slot >= 0) {
-        const int t = block_inverse_cdf(from_p, V, u64, sums);
+        // init_mode 3: the last row of this step; init_mode 4: the distribution of the token one image row above
+        const float *src = e_new + (long)(Le - 1) * V;
+        uint64_t Zs = Z_new[Le - 1];
+        if (init_mode == 4) {
+            int src_new;
+            const int code = above_source(new_slot, d.n_img[s], a, Le, row_width, &src_new);
+            if (code == kRefUniform) return;   // a uniform draft: the window update makes it
+            if (src_new >= 0) { src = e_new + (long)src_new * V; Zs = Z_new[src_new]; }
+            else if (code >= 0) { src = e_new + (long)code * V; Zs = Z_new[code]; }
+            else src = ref_row_ptr(d, s, code, e_ref, Z_ref, row_width, Zs);
+        }
+        auto from_src = [&](int v) { return weight_of(src[v]); };
+        const int t = block_inverse_cdf(from_src, V, u64, sums);
         if (threadIdx.x == 0) d.cand_new[s * L + new_slot] = d.lo + t;
         return;
     }
+    const float *pk = e_new + (long)k * V;
+    const uint64_t Zp = Z_new[k];
+    auto from_p = [&](int v) { return weight_of(pk[v]); };
 
     int tok;
     if (k == a && a < Le - 1) {
         const int rr = d.ref_row[s * L + a + 1];
-        const float *qrow = rr < 0 ? nullptr : e_ref + (long)rr * V;
-        const uint64_t Zq = rr < 0 ? (uint64_t)V : Z_ref[rr];
+        uint64_t Zq;
+        const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
         const int x = d.win_tok[s * L + a + 1] - d.lo;
         auto resid = [&](int v) {
             double P = prob(weight_of(pk[v]), Zp);
@@ -516,8 +559,9 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
     } else if (k > a && k <= Le - 2) {
         const int x = d.win_tok[s * L + k + 1] - d.lo;
         const int rr = d.ref_row[s * L + k + 1];
-        const uint64_t wq = rr < 0 ? 1ull : weight_of(e_ref[(long)rr * V + x]);
-        const uint64_t Zq = rr == kRefOneHot ? 1ull : (rr < 0 ? (uint64_t)V : Z_ref[rr]);
+        uint64_t Zq;
+        const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
+        const uint64_t wq = qrow ? weight_of(qrow[x]) : 1ull;
         if (keep_rule(tau, weight_of(pk[x]), Zp, wq, Zq)) {
             tok = x;
         } else {
@@ -586,6 +630,10 @@ __global__ void commit_kernel(DecideState d, uint64_t seed, int init_mode, int r
                 } else if (init_mode == 3) {
                     tok = d.cand_new[s * L + k2];
                     ref = Le - 1;
+                } else if (init_mode == 4) {
+                    int src_new;
+                    ref = above_source(k2, n_img, a, Le, row_width, &src_new);
+                    tok = ref == kRefUniform ? uniform_of(k) : d.cand_new[s * L + k2];
                 } else {
                     tok = uniform_of(k);
                 }
@@ -607,6 +655,21 @@ __global__ void commit_kernel(DecideState d, uint64_t seed, int init_mode, int r
         res->reject_index = a < Le - 1 ? a + 1 : -1;
         res->done = remaining == 0 ? 1 : 0;
     }
+}
+
+// init_mode 4: image token n_img + i became final under row i of this step (i <= a).  One block per (sequence, i);
+// where several of them share a slot of the ring (row_width <= a) the last one is the one kept.
+__global__ void keep_rows_kernel(DecideState d, int row_width) {
+    const int L = d.L, V = d.V, s = blockIdx.x / L, i = blockIdx.x % L;
+    if (d.Le[s] == 0) return;
+    const int a = d.acc_len[s];
+    if (i > a || i + row_width <= a) return;
+    const uint32_t step = *d.step;
+    const float *src = d.e_buf[step & 1u] + ((long)s * L + i) * V;
+    const int h = (d.n_img[s] + i) % row_width;
+    float *dst = d.hist_e + ((long)s * row_width + h) * V;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) dst[v] = src[v];
+    if (threadIdx.x == 0) d.hist_Z[s * row_width + h] = d.Z_buf[step & 1u][s * L + i];
 }
 
 __global__ void philox_fill_kernel(uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n) {
@@ -676,18 +739,24 @@ hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const flo
 }
 
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    verify_kernel<<<n_seqs, 256, 0, st>>>(d, sp.seed);
+    verify_kernel<<<n_seqs, 256, 0, st>>>(d, sp.seed, sp.row_width);
     return hipGetLastError();
 }
 
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    const int rows_per_seq = sp.init_mode == 3 ? 2 * d.L : d.L;
-    draw_kernel<<<n_seqs * rows_per_seq, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq);
+    const int rows_per_seq = sp.init_mode >= 3 ? 2 * d.L : d.L;
+    draw_kernel<<<n_seqs * rows_per_seq, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq,
+                                                                                                 sp.init_mode, sp.row_width);
     return hipGetLastError();
 }
 
 hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
     commit_kernel<<<n_seqs, 64, 0, st>>>(d, sp.seed, sp.init_mode, sp.row_width);
+    return hipGetLastError();
+}
+
+hipError_t launch_keep_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
+    keep_rows_kernel<<<n_seqs * d.L, 256, 0, st>>>(d, sp.row_width);
     return hipGetLastError();
 }
 

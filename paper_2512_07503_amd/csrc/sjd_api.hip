@@ -594,6 +594,10 @@ int alloc_state(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &d.acc_len, (size_t)S * 4))) return rc;
     if ((rc = dev_alloc(c, &d.cand, (size_t)S * L * 4))) return rc;
     if ((rc = dev_alloc(c, &d.cand_new, (size_t)S * L * 4))) return rc;
+    if (c->sp.init_mode == 4) {
+        if ((rc = dev_alloc(c, &d.hist_e, (size_t)S * c->sp.row_width * c->Vs * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &d.hist_Z, (size_t)S * c->sp.row_width * sizeof(uint64_t)))) return rc;
+    }
     if ((rc = dev_alloc(c, &d.step, 4))) return rc;
     for (int b = 0; b < 2; ++b) {
         if ((rc = dev_alloc(c, &d.e_buf[b], (size_t)S * L * c->Vs * sizeof(float)))) return rc;
@@ -646,9 +650,9 @@ int validate_desc(const sjd_model_desc *md, const sjd_weights *w, const sjd_samp
         sjd_set_error(err, "bf16 needs head_dim %% 32 == 0, d_model %% 16 == 0, d_ff %% 16 == 0"); return SJD_EINVAL;
     }
     if (!(md->rms_eps > 0.0f) || !(md->rope_theta > 0.0f)) { sjd_set_error(err, "bad rms_eps / rope_theta"); return SJD_EINVAL; }
-    if (sp->top_k < 1 || !(sp->temperature > 0.0f) || sp->init_mode < 0 || sp->init_mode > 3 ||
-        (sp->init_mode == 2 && sp->row_width < 1) || sp->reuse_tau != sp->reuse_tau || sp->reuse_tau < 0.0f) {
-        sjd_set_error(err, "bad sampling parameters (top_k >= 1, temperature > 0, tau >= 0, init_mode 0..3, row_width >= 1 for init_mode 2)"); return SJD_EINVAL;
+    if (sp->top_k < 1 || !(sp->temperature > 0.0f) || sp->init_mode < 0 || sp->init_mode > 4 ||
+        ((sp->init_mode == 2 || sp->init_mode == 4) && sp->row_width < 1) || sp->reuse_tau != sp->reuse_tau || sp->reuse_tau < 0.0f) {
+        sjd_set_error(err, "bad sampling parameters (top_k >= 1, temperature > 0, tau >= 0, init_mode 0..4, row_width >= 1 for init_mode 2 and 4)"); return SJD_EINVAL;
     }
     if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm ||
         !w->w_gate || !w->w_up || !w->w_down) {
@@ -661,6 +665,7 @@ int run_decide(sjd_ctx *c) {
     SJD_LAUNCH(c, KC_SAMPLE_ROWS, launch_sample_rows(c->stream, c->ds, c->sp, c->logits, c->n_seqs));
     SJD_LAUNCH(c, KC_VERIFY, launch_verify(c->stream, c->ds, c->sp, c->n_seqs));
     SJD_LAUNCH(c, KC_DRAW, launch_draw(c->stream, c->ds, c->sp, c->n_seqs));
+    if (c->sp.init_mode == 4) SJD_LAUNCH(c, KC_COMMIT, launch_keep_rows(c->stream, c->ds, c->sp, c->n_seqs));
     SJD_LAUNCH(c, KC_COMMIT, launch_commit(c->stream, c->ds, c->sp, c->n_seqs));
     return SJD_OK;
 }

@@ -45,7 +45,8 @@ def test_create_rejects_bad_arguments_on_the_host():
         assert not ctx.value
         assert L.sjd_last_error(None)
     for bad_sp in (Sampling(3.0, 1.0, 0, 0.5, 0, 0), Sampling(3.0, 0.0, 5, 0.5, 0, 0), Sampling(3.0, 1.0, 5, -1.0, 0, 0),
-                   Sampling(3.0, 1.0, 5, 0.5, 0, 4), Sampling(3.0, 1.0, 5, 0.5, 0, -1), Sampling(3.0, 1.0, 5, 0.5, 0, 2, 0),
+                   Sampling(3.0, 1.0, 5, 0.5, 0, 5), Sampling(3.0, 1.0, 5, 0.5, 0, -1), Sampling(3.0, 1.0, 5, 0.5, 0, 2, 0),
+                       Sampling(3.0, 1.0, 5, 0.5, 0, 4, 0),
                        Sampling(3.0, 1.0, 5, float("nan"), 0, 0)):
         assert L.sjd_create(C.byref(ModelDesc(**good)), C.byref(w), C.byref(bad_sp), None, C.byref(ctx)) == sjd.binding.EINVAL
     w0 = Weights(0, 1, 1, *[C.cast(arr, C.POINTER(C.c_void_p))] * 9)

@@ -80,10 +80,12 @@ def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
                                                      ("small_f32", 3, 0, None), ("small_sub", 1, 0, float("inf")),
                                                      ("small_sub", 2, 2, None), ("small_sub", 3, 0, 0.0),
                                                      ("small_fused64", 1, 0, None), ("small_fused64", 2, 5, None),
-                                                     ("small_fused64", 3, 0, None)])
+                                                     ("small_fused64", 3, 0, None),
+                                                     ("small_f32", 4, 3, None), ("small_f32", 4, 12, None), ("small_f32", 4, 1, None),
+                                                     ("small_sub", 4, 2, float("inf")), ("small_fused64", 4, 5, None)])
 def test_spatial_initialisation_step_by_step(oracle, name, mode, row_width, tau):
-    """Sec. 4.2: new window slots copied from the left / upper neighbour (one-hot reference) or drawn from the
-    neighbour's row; tokens AND references of every window must equal the oracle's at every step."""
+    """Sec. 4.2: new window slots copied from the left / upper neighbour (one-hot reference) or drawn from the left /
+    upper neighbour's distribution; tokens AND references of every window must equal the oracle's at every step."""
     cfg = workload.get_config(name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, tau=tau, head_alpha=6.0, std=0.08, init_mode=mode, row_width=row_width)
     f32 = cfg["dtype"] == "f32"

@@ -134,7 +134,7 @@ def test_no_reuse_decoding_has_the_autoregressive_joint_law(oracle):
     _chi_square_against(joint, counts, n, 30)
 
 
-@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 2), (3, 0)])
+@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 2), (3, 0), (4, 2)])
 def test_spatial_initialisation_keeps_the_autoregressive_joint_law(oracle, mode, row_width):
     """Sec. 4.2: however a new slot is initialised (copy of the left or upper neighbour with a one-hot reference, a
     draw from the neighbour's row with that row as reference), verification against the true proposal keeps the
@@ -150,11 +150,13 @@ def test_spatial_initialisation_keeps_the_autoregressive_joint_law(oracle, mode,
     _chi_square_against(joint, counts, n, 40)
 
 
-@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 3), (3, 0)])
+@pytest.mark.parametrize("mode,row_width", [(1, 0), (2, 3), (3, 0), (4, 3), (4, 9)])
 def test_spatial_initialisation_fills_new_slots_as_stated(oracle, mode, row_width):
     """New slots of the window after a step: (a) equal the token to their left, (b) equal the token row_width places
     back in the image (uniform in the first image row), both with the one-hot reference; (c) are the inverse-CDF
-    draws from the last row of the step with that row as reference.  Slots of the first window are uniform."""
+    draws from the last row of the step with that row as reference; (d) are draws from the row under which the token
+    row_width places back became final (recomputed here from the logits of the step that finalised it), or from the
+    reference of the draft at that place.  Slots of the first window are uniform."""
     cfg, arch, w, cond, uncond = _model("small_f32")
     L, Vs, lo, N, K = 6, arch["sample_hi"] - arch["sample_lo"], arch["sample_lo"], 40, 60
     P = cfg["prompt_len"]
@@ -167,11 +169,15 @@ def test_spatial_initialisation_fills_new_slots_as_stated(oracle, mode, row_widt
             words = oracle.philox([0, k, 0, 0], [seed, 0])
             assert toks[k] == lo + ((words[3] * Vs) >> 32) and refs[k] == -1
         step = 0
+        final_row = {}                             # image index -> (e, Z) of the row under which it became final
         while True:
             step += 1
             Le = dec.window()[2]
             logits = dec.peek_logits()
+            n_before = len(dec.tokens())
             res = dec.step()[0]
+            for i in range(res["n_finalized"]):
+                final_row[n_before + i] = oracle.sampling_row(logits[0, 0, i], logits[0, 1, i], 3.0, 1.0, K)
             if res["done"]:
                 break
             a = res["n_accepted"]
@@ -193,10 +199,25 @@ def test_spatial_initialisation_fills_new_slots_as_stated(oracle, mode, row_widt
                     else:
                         words = oracle.philox([step, k, 0, 0], [seed, 0])
                         assert after[k2] == lo + ((words[3] * Vs) >> 32) and refs[k2] == -1
-                else:
+                elif mode == 3:
                     e, Z = oracle.sampling_row(logits[0, 0, Le - 1], logits[0, 1, Le - 1], 3.0, 1.0, K)
                     words = oracle.philox([step, k, 0, 0], [seed, 0])
                     assert after[k2] == lo + oracle.draw(e, Z, (words[1] << 32) | words[2]) and refs[k2] == Le - 1
+                else:
+                    up = idx - row_width
+                    words = oracle.philox([step, k, 0, 0], [seed, 0])
+                    if up < 0:
+                        assert after[k2] == lo + ((words[3] * Vs) >> 32) and refs[k2] == -1
+                    elif up < n_img:
+                        e, Z = final_row[up]
+                        assert refs[k2] == -3 - up % row_width
+                        assert after[k2] == lo + oracle.draw(e, Z, (words[1] << 32) | words[2])
+                    else:
+                        j = up - n_img + 1            # the place above is slot j of this window: same distribution
+                        assert refs[k2] == refs[j]
+                        if refs[j] >= 0:
+                            e, Z = oracle.sampling_row(logits[0, 0, refs[j]], logits[0, 1, refs[j]], 3.0, 1.0, K)
+                            assert after[k2] == lo + oracle.draw(e, Z, (words[1] << 32) | words[2])
     assert seen > 20
 
 
