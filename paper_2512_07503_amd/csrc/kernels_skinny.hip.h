@@ -24,6 +24,15 @@
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PARTIAL = 4 };
 
+// Where row m of the QKV projection goes.  The operand layouts of queries, keys and values are all of the form
+// f(row) + g(head dimension), so everything that depends on the row alone is worked out once per row:
+struct QkvRow {
+    int pos;    // absolute position (rotary angle), -1 for a row that is not computed
+    int q_off;  // element offset of this row in the query buffer of head 0: sequence segment and window index
+    int page;   // KV page of the position
+    int k_off;  // row part of the element offset inside a (page, head) block of keys
+    int v_off;  // same for values
+};
 struct SkinnyArgs {
     const bf16_t *A;   // [MT][KB][64][8] raw activations, fragment-major
     const bf16_t *W;   // [groups * NBW][KB][64][8]
@@ -35,9 +44,9 @@ struct SkinnyArgs {
     float *x;          // [M][N] fp32 residual stream, updated in place
     bf16_t *xb;        // the same in bf16, fragment-major [M][N]
     int N;             // also the logits row length for HEAD
-    // QKV
-    const int32_t *row_tok, *row_pos;
-    const float *rope_cos, *rope_sin;
+    // QKV: per-row tables written once per forward by embed_dual_kernel (no dependent loads in the projections)
+    const QkvRow *row_meta;   // [M]
+    const float2 *row_rot;    // [M][hd / 2] (cos, sin) of the row's position; (1, 0) for rows that are not computed
     bf16_t *q_out;
     KvPool pool;
     int L, H, Hkv, hd;
@@ -49,47 +58,32 @@ struct SkinnyArgs {
     // PARTIAL: K split across workgroups (grid.y = ksplit), plain partial sums; the other epilogues run with ksplit 1
     int ksplit, kb_per_split;
     float *part;             // [ksplit][M][N]
+    // L2 warm-up of the NEXT projection's weights: workgroups [groups, groups + pf_wgs) of a launch with one row
+    // group and whole K only touch memory.  The next launch's workgroup g' will read slab g' (pf_slab_bytes at
+    // pf_base + g' * pf_slab_bytes, g' < pf_groups) and runs on XCD g' % 8, whose L2 the touching workgroup shares.
+    const char *pf_base;
+    uint32_t pf_slab_bytes;
+    int pf_groups, pf_wgs;   // pf_wgs: a multiple of 8, 0 = none
+    uint32_t *pf_sink;       // a device word nobody reads; a (practically never taken) store to it keeps the loads alive
 #ifdef SJD_PHASE_TIMING
     unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
 #endif
 };
 
-// Where row m of the QKV projection goes.  The operand layouts of queries, keys and values are all of the form
-// f(row) + g(head dimension), so everything that depends on the row alone is worked out once per row:
-struct QkvRow {
-    int pos;    // absolute position (rotary angle), -1 for a row that is not computed
-    int q_off;  // element offset of this row in the query buffer of head 0: sequence segment and window index
-    int page;   // KV page of the position
-    int k_off;  // row part of the element offset inside a (page, head) block of keys
-    int v_off;  // same for values
-};
-SJD_D QkvRow qkv_row(const SkinnyArgs &a, int m) {
-    QkvRow r;
-    if (a.row_tok[m] < 0) {
-        r.pos = -1; r.q_off = 0; r.page = 0; r.k_off = 0; r.v_off = 0;
-        return r;
-    }
-    const int seg = m / a.L, i_win = m % a.L;
-    r.pos = a.row_pos[m];
-    r.q_off = seg * a.H * (int)Layout<bf16_t>::q_elems(a.L, a.hd) + (int)Layout<bf16_t>::q_index(i_win, 0, a.hd);
-    r.page = a.pool.page_table[seg * a.pool.pages_per_seg + r.pos / a.pool.page_tokens];
-    const int t = r.pos % a.pool.page_tokens;
-    r.k_off = (int)Layout<bf16_t>::k_index(t, 0, a.hd);
-    r.v_off = (int)Layout<bf16_t>::v_index(t, 0, a.hd);
-    return r;
-}
+SJD_D QkvRow qkv_row(const SkinnyArgs &a, int m) { return a.row_meta[m]; }
 // Column group g = (head, sub-block of 32 dimensions); v0 / v1 are dimensions j0 = 32 sub + col and j0 + hd / 2 of
 // that head (a rotary pair): rotate q and k, then queries to the attention operand layout, keys / values into
 // their page.
-// (cos, sin) of the rotation that qkv_store applies to this element pair: (1, 0) for value heads and idle rows
-SJD_D void qkv_rotation(const SkinnyArgs &a, const QkvRow &r, int g, int col, float &c, float &s) {
+// (cos, sin) of the rotation that qkv_store applies to this element pair of row m: (1, 0) for value heads
+SJD_D void qkv_rotation(const SkinnyArgs &a, int m, int g, int col, float &c, float &s) {
     const int pairs = a.hd >> 6;
     const int head = g / pairs, sub = g % pairs, half = a.hd >> 1;
     c = 1.0f;
     s = 0.0f;
-    if (r.pos >= 0 && head < a.H + a.Hkv) {
-        c = a.rope_cos[(size_t)r.pos * half + sub * 32 + col];
-        s = a.rope_sin[(size_t)r.pos * half + sub * 32 + col];
+    if (head < a.H + a.Hkv) {
+        const float2 cs = a.row_rot[(size_t)m * half + sub * 32 + col];
+        c = cs.x;
+        s = cs.y;
     }
 }
 SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float v0, float v1, float c, float s) {
@@ -158,10 +152,32 @@ SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, c
     }
 }
 
+// Workgroup `id` (linear, >= first_id) of a launch reads one word of every 128-byte line of its share of the next
+// launch's weight slabs, which brings the lines into the L2 of the XCD it runs on.  Workgroups go to XCDs round-robin
+// by linear id, so it takes slabs g' with g' % 8 == id % 8; the pf_wgs / 8 workgroups of one XCD split those evenly.
+SJD_D void l2_warm_next(const SkinnyArgs &a, int id, int first_id, int tid, int threads) {
+    const int xcd = id & 7, rank = (id - first_id) >> 3, ranks = a.pf_wgs >> 3;
+    const int n_slabs = a.pf_groups > xcd ? (a.pf_groups - xcd + 7) >> 3 : 0;
+    const uint32_t lines_per_slab = a.pf_slab_bytes >> 7;
+    const uint32_t total = (uint32_t)n_slabs * lines_per_slab, per = (total + ranks - 1) / ranks;
+    const uint32_t lo = rank * per, hi = lo + per < total ? lo + per : total;
+    uint32_t sink = 0;
+#pragma unroll 8
+    for (uint32_t i = lo + tid; i < hi; i += threads) {
+        const uint32_t s = i / lines_per_slab, l = i - s * lines_per_slab;
+        sink ^= *reinterpret_cast<const uint32_t *>(a.pf_base + (size_t)(xcd + 8 * s) * a.pf_slab_bytes + (size_t)l * 128);
+    }
+    if (sink == 0x9e3779b9u) *a.pf_sink = sink;  // a word nobody reads; the store only keeps the loads alive
+}
+
 template <int MT, int NBW, int NW, int DEPTH, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
+    if (a.pf_wgs > 0 && (int)blockIdx.x >= a.groups) {  // whole workgroup: only touches the next launch's weights
+        l2_warm_next(a, blockIdx.x, a.groups, tid, NW * 64);
+        return;
+    }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
     // blockIdx.x enumerates (column group g, row group mg).  With several row groups the order is chosen so that
     // the row groups of one column group are dispatched close together AND to the same XCD (workgroups go to
@@ -214,8 +230,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                     }
                 } else {
                     qrow[j][hh].pos = -1;
-                    if (m < a.M) qrow[j][hh] = qkv_row(a, m);
-                    qkv_rotation(a, qrow[j][hh], g, lane & 31, rot_c[j][hh], rot_s[j][hh]);
+                    rot_c[j][hh] = 1.0f;
+                    rot_s[j][hh] = 0.0f;
+                    if (m < a.M) {
+                        qrow[j][hh] = qkv_row(a, m);
+                        qkv_rotation(a, m, g, lane & 31, rot_c[j][hh], rot_s[j][hh]);
+                    }
                 }
             }
     }
@@ -231,12 +251,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
     for (int j = 0; j < MT; ++j) ssq[j] = 0.0f;
 
-    // Ring of DEPTH slots.  The loop body is branch-free so that the compiler can count outstanding loads
-    // exactly (a slot is consumed while the DEPTH - 1 younger ones are still in flight): iterations past the
-    // end re-read the last fragment (a cache hit) and contribute nothing because their A operand is zeroed.
+    // Ring of DEPTH slots; a wavefront with fewer than DEPTH iterations fills the spare slots with its last
+    // fragment (never consumed).
     if (n_it > 0) {
         u32x4 bq[DEPTH][NBW], aq[DEPTH][MT];
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
             const size_t kb = (size_t)(kb_lo + wave + (s < n_it ? s : n_it - 1) * NW);
@@ -246,37 +264,58 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
         }
         __builtin_amdgcn_sched_barrier(0);
-        for (int it0 = 0; it0 < n_it; it0 += DEPTH) {
+        auto consume = [&](int s) {
+#pragma unroll
+            for (int j = 0; j < MT; ++j) {
+                const u32x4 araw = aq[s][j];
+                const bf16x8 av = __builtin_bit_cast(bf16x8, araw);
+                if (kNorm) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t pr = araw[e];
+                        const float lo = __builtin_bit_cast(float, pr << 16), hi = __builtin_bit_cast(float, pr & 0xFFFF0000u);
+                        ssq[j] = fmaf(lo, lo, ssq[j]);
+                        ssq[j] = fmaf(hi, hi, ssq[j]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < NBW; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq[s][i]), acc[j][i], 0, 0, 0);
+            }
+        };
+        auto refill = [&](int s, int it) {
+            const size_t kb = (size_t)(kb_lo + wave + it * NW);
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
+#pragma unroll
+            for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+        };
+        // Steady state: groups of DEPTH iterations whose refills are all fragments that will be used.  The body is
+        // branch-free so that the compiler counts outstanding loads exactly (a slot is consumed while the
+        // DEPTH - 1 younger ones are still in flight).
+        int it0 = 0;
+        for (; it0 + 2 * DEPTH <= n_it; it0 += DEPTH) {
 #pragma unroll
             for (int s = 0; s < DEPTH; ++s) {
-                const int it = it0 + s;
-                const bool valid = it < n_it;
-#pragma unroll
-                for (int j = 0; j < MT; ++j) {
-                    const u32x4 araw = valid ? aq[s][j] : zero4;
-                    const bf16x8 av = __builtin_bit_cast(bf16x8, araw);
-                    if (kNorm) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t pr = araw[e];
-                            const float lo = __builtin_bit_cast(float, pr << 16), hi = __builtin_bit_cast(float, pr & 0xFFFF0000u);
-                            ssq[j] = fmaf(lo, lo, ssq[j]);
-                            ssq[j] = fmaf(hi, hi, ssq[j]);
-                        }
-                    }
-#pragma unroll
-                    for (int i = 0; i < NBW; ++i)
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bq[s][i]), acc[j][i], 0, 0, 0);
-                }
-                const int nx = it + DEPTH;
-                const size_t kb = (size_t)(kb_lo + wave + (nx < n_it ? nx : n_it - 1) * NW);
-#pragma unroll
-                for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
-#pragma unroll
-                for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+                consume(s);
+                refill(s, it0 + s + DEPTH);
                 __builtin_amdgcn_sched_barrier(0);  // keep the refill here: the scheduler must not sink it towards its use
             }
         }
+        // The last n_it - it0 < 2 DEPTH iterations: refill only what is still needed (the conditions are
+        // wavefront-uniform), then drain.  Every fragment is loaded exactly once: with the weights already in L2 the
+        // loop is bound by what the CU's L1 delivers, so a redundant load costs as much as a useful one.
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            if (it0 + s < n_it) {
+                consume(s);
+                if (it0 + s + DEPTH < n_it) refill(s, it0 + s + DEPTH);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s)
+            if (it0 + DEPTH + s < n_it) consume(s);
     }
 
     SJD_STAMP(1);
@@ -340,11 +379,39 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     SJD_STAMP(3);
 }
 
-// Embedding gather for the fused path: fp32 residual stream + its bf16 fragment-major copy.
+// Embedding gather for the fused path: fp32 residual stream + its bf16 fragment-major copy.  The block of row m
+// also writes the row's entry of the tables that every QKV projection of this forward reads: destination offsets
+// (sequence segment, window index, KV page of the position) and the rotary (cos, sin) of the position.
+struct RowTables {
+    const int32_t *row_pos;
+    const float *rope_cos, *rope_sin;   // [max_ctx][hd / 2]
+    const int32_t *page_table;
+    int pages_per_seg, page_tokens, L, H, hd;
+    QkvRow *meta;
+    float2 *rot;
+};
 __global__ void embed_dual_kernel(const bf16_t *__restrict__ emb, const int32_t *__restrict__ row_tok, float *__restrict__ x,
-                                  bf16_t *__restrict__ xb, int d) {
+                                  bf16_t *__restrict__ xb, int d, RowTables t) {
     const int m = blockIdx.x;
     const int tok = row_tok[m];
+    const int half = t.hd >> 1;
+    const int pos = tok >= 0 ? t.row_pos[m] : -1;
+    if (threadIdx.x == 0) {
+        QkvRow r;
+        r.pos = pos; r.q_off = 0; r.page = 0; r.k_off = 0; r.v_off = 0;
+        if (pos >= 0) {
+            const int seg = m / t.L, i_win = m % t.L;
+            r.q_off = seg * t.H * (int)Layout<bf16_t>::q_elems(t.L, t.hd) + (int)Layout<bf16_t>::q_index(i_win, 0, t.hd);
+            r.page = t.page_table[seg * t.pages_per_seg + pos / t.page_tokens];
+            const int tk = pos % t.page_tokens;
+            r.k_off = (int)Layout<bf16_t>::k_index(tk, 0, t.hd);
+            r.v_off = (int)Layout<bf16_t>::v_index(tk, 0, t.hd);
+        }
+        t.meta[m] = r;
+    }
+    for (int j = threadIdx.x; j < half; j += blockDim.x)
+        t.rot[(size_t)m * half + j] = pos >= 0 ? make_float2(t.rope_cos[(size_t)pos * half + j], t.rope_sin[(size_t)pos * half + j])
+                                               : make_float2(1.0f, 0.0f);
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
         const bf16_t v = tok >= 0 ? emb[(size_t)tok * d + i] : (bf16_t)0;
         x[(size_t)m * d + i] = bf16_to_float(v);
@@ -400,10 +467,14 @@ __global__ void resid_reduce_kernel(const float *__restrict__ part, int ksplit, 
 
 template <int EPI, int NW>
 inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int MT, int groups, int nbw) {
-    constexpr int DEPTH = 8;
+#ifndef SJD_SKINNY_DEPTH
+#define SJD_SKINNY_DEPTH 8
+#endif
+    constexpr int DEPTH = SJD_SKINNY_DEPTH;
     SkinnyArgs a = a_in;
     a.groups = groups;
-    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1), a.ksplit);
+    if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = 0;
+    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1) + a.pf_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
                 if constexpr (EPI == EPI_QKV) {
                     const QkvRow &r = qrow[(wave * 2 + j) * 32 + row];
                     float c, sn;
-                    qkv_rotation(a, r, g, col, c, sn);
+                    qkv_rotation(a, m, g, col, c, sn);
                     qkv_store(a, r, g, col, vals[0] * inv, vals[1] * inv, c, sn);
                 } else {
                     float xin[2] = {0.0f, 0.0f};

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -73,6 +74,10 @@ struct sjd_ctx {
     int attn_chunk = 0, attn_nchunks = 0;
     bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
     float *part_o = nullptr, *part_ml = nullptr;
+    QkvRow *row_meta = nullptr;            // per-row tables of the fused path, rewritten by every forward
+    float2 *row_rot = nullptr;
+    bool l2_warm = true;                   // projection launches touch the next projection's weights
+    uint32_t *pf_sink = nullptr;
     float *skinny_part = nullptr;          // partial tiles of K-split fused projections
     size_t skinny_part_elems = 0;
     bool fused = false;  // small-M path: fused projection kernels, RMSNorm gains folded into the weights
@@ -300,17 +305,19 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     const int MT = M <= 64 ? ceil_div(M, 32) : 2;
     hipStream_t st = c->stream;
     SJD_LAUNCH(c, KC_EMBED, after([&] {
-                   embed_dual_kernel<<<M, 256, 0, st>>>((const bf16_t *)c->tok_emb, c->rm.row_tok, c->x, (bf16_t *)c->xn, d);
+                   RowTables rt;
+                   rt.row_pos = c->rm.row_pos; rt.rope_cos = c->rope_cos; rt.rope_sin = c->rope_sin;
+                   rt.page_table = c->page_table; rt.pages_per_seg = c->pps; rt.page_tokens = c->pt;
+                   rt.L = c->L; rt.H = H; rt.hd = hd; rt.meta = c->row_meta; rt.rot = c->row_rot;
+                   embed_dual_kernel<<<M, 256, 0, st>>>((const bf16_t *)c->tok_emb, c->rm.row_tok, c->x, (bf16_t *)c->xn, d, rt);
                }));
     SkinnyArgs a;
     memset(&a, 0, sizeof a);
     a.M = M;
     a.m_groups = m_groups;
     a.eps = md.rms_eps;
-    a.row_tok = c->rm.row_tok;
-    a.row_pos = c->rm.row_pos;
-    a.rope_cos = c->rope_cos;
-    a.rope_sin = c->rope_sin;
+    a.row_meta = c->row_meta;
+    a.row_rot = c->row_rot;
     a.q_out = (bf16_t *)c->q;
     a.L = c->L; a.H = H; a.Hkv = Hkv; a.hd = hd; a.F = F;
     a.x = c->x;
@@ -332,8 +339,26 @@ int forward_fused(sjd_ctx *c, bool with_head) {
                       ((md.kernel_flags & SJD_KERNELS_TILES) || ceil_div((H + 2 * Hkv) * (hd / 64) * 2, 4) * ceil_div(M, TILE_M) >= 96);
     // output / down projection: x += A W^T.  One kernel when a workgroup's share is small, else K split over
     // grid.y with the partial sums added by resid_reduce_kernel after the kernel boundary.
-    auto resid = [&](int cls, const void *A, const void *W, int K) -> int {
+    // Every few-row projection launch carries extra workgroups that touch the weights of the projection after it,
+    // so that those are in the L2 of the XCD that will read them when that launch starts (the launches are short
+    // and latency-bound: first touch from HBM costs 2-3x the time of an L2 hit, and the chip is mostly idle).
+    struct Proj { const void *W; int groups, nbw, KB; bool whole; };
+    const int groups_d = ceil_div(ceil_div(d, 32), nbw_d), groups_qkv = (H + 2 * Hkv) * (hd / 64);
+    auto resid_whole = [&](int K) { return (double)(nbw_d * 32 + MT * 32) * K * 2.0 <= 512e3; };
+    auto warm = [&](int cur_groups, const Proj &nx) {
+        a.pf_wgs = 0;
+        if (!c->l2_warm || tile || m_groups > 1 || !nx.whole || !nx.W) return;
+        const uint32_t slab = (uint32_t)nx.nbw * nx.KB * 1024;
+        const int fit = (int)std::min<size_t>(nx.groups, ((size_t)24 << 20) / slab);   // what the L2s hold beside the current weights
+        int wgs = (int)(((size_t)fit * slab / (96 << 10) + 7) / 8 * 8);
+        wgs = std::min(wgs, (256 - cur_groups) / 8 * 8);
+        if (wgs < 8 || fit < 1) return;
+        a.pf_base = (const char *)nx.W; a.pf_slab_bytes = slab; a.pf_groups = fit; a.pf_wgs = wgs; a.pf_sink = c->pf_sink;
+    };
+    const Proj none = {nullptr, 0, 0, 0, false};
+    auto resid = [&](int cls, const void *A, const void *W, int K, const Proj &nx) -> int {
         a.A = (const bf16_t *)A; a.W = (const bf16_t *)W; a.KB = K / 16; a.N = d;
+        a.pf_wgs = 0;
         if (tile) {
             const int n_blocks = ceil_div(d, 64) * 2, wgs = ceil_div(n_blocks, 4) * ceil_div(M, TILE_M);
             int ks = std::min(8, std::max(1, 256 / wgs));
@@ -361,7 +386,9 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         }
         if (ks == 1) {
             whole_k();
+            warm(groups, nx);
             SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
+            a.pf_wgs = 0;
             return SJD_OK;
         }
         a.kb_per_split = ceil_div(a.KB, ks);
@@ -389,19 +416,26 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2));
         } else {
             whole_k();
-            SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, (H + 2 * Hkv) * (hd / 64), 2, nw_for((H + 2 * Hkv) * (hd / 64))));
+            warm(groups_qkv, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, groups_qkv, 2, nw_for(groups_qkv)));
+            a.pf_wgs = 0;
         }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
-        { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd); if (rc) return rc; }
+        { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd, Proj{lw.wgu, F / 32, 2, d / 16, true}); if (rc) return rc; }
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
         if (tile) {
             whole_k();
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2));
         } else {
             whole_k();
+            warm(F / 32, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+            a.pf_wgs = 0;
         }
-        { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F); if (rc) return rc; }
+        const Proj after_down = l + 1 < md.n_layers ? Proj{c->layers[l + 1].wqkv, groups_qkv, 2, d / 16, true}
+                                : with_head         ? Proj{c->lm_head, ceil_div(ceil_div(c->Vs, 32), 2), 2, d / 16, true}
+                                                    : none;
+        { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F, after_down); if (rc) return rc; }
     }
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
@@ -558,6 +592,10 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         const int widest = std::max(std::max((H + 2 * Hkv) * (hd / 64), F / 32), ceil_div(c->Vs, 64));
         c->skinny_part_elems = std::max((size_t)widest * 8 * (2 * 2 * 1024 + 64), (size_t)8 * M * d);
         if ((rc = dev_alloc(c, &c->skinny_part, c->skinny_part_elems * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_sink, 256))) return rc;
+        if ((rc = dev_alloc(c, &c->row_meta, (size_t)M * sizeof(QkvRow)))) return rc;
+        if ((rc = dev_alloc(c, &c->row_rot, (size_t)M * (hd / 2) * sizeof(float2)))) return rc;
+        if (const char *e = getenv("SJD_L2_WARM")) c->l2_warm = atoi(e) != 0;
     }
     if (c->attn_mfma) {
         // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
