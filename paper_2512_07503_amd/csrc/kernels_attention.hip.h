@@ -107,6 +107,9 @@ __global__ void pack_q_kernel(const T *__restrict__ src, T *__restrict__ dst, in
 // (Layout<bf16_t>::v_index).  Keys and values stream from HBM exactly once per (segment, kv head):
 // the G query heads of a kv head run as G wavefronts of one workgroup and share the fetches in L1/L2.
 // Chunks are merged by attention_combine_kernel.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 hw_bf16x2_t __attribute__((ext_vector_type(2)));
+
 struct AttnArgs {
     const bf16_t *q;       // [segments][H][q_elems(L, hd)]
     KvPool pool;
@@ -118,6 +121,9 @@ struct AttnArgs {
     bf16_t *out_act;         // [M][H * hd] GEMM-operand layout
     float *out_plain;        // optional [M][H][hd]
     int L, H, Hkv, hd, chunk, n_chunks;
+#ifdef SJD_PHASE_TIMING
+    unsigned long long *phase;  // [workgroups][8] wall-clock stamps (profiling builds only)
+#endif
     int n_qt;                // query tiles of 32 window rows = ceil(L / 32)
     float scale_log2e;       // 1 / sqrt(hd) * log2(e)
 };
@@ -125,7 +131,7 @@ struct AttnArgs {
 // One wavefront's pass over the 32-token blocks t_begin, t_begin + t_stride, ... < t_end of (segment seg, query
 // head h, query tile qt): leaves the unnormalised O^T in o, the running maximum (base-2 logits) in m_run and this
 // lane's half of the running sum in l_run; window row = 32 qt + lane % 32.
-template <int HD>
+template <int HD, int D>
 SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int qt, int t_begin, int t_end, int t_stride, int kv, int n_tot, int lane,
                           f32x16 (&o)[HD / 32], float &m_run, float &l_run) {
     constexpr int KF = HD / 16, DB = HD / 32;
@@ -155,54 +161,62 @@ SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int qt, in
     l_run = 0.0f;
     if (t_begin >= t_end) return;
     const int query = 32 * qt + (lane & 31);
+    const int last_vis = kv + query < n_tot - 1 ? kv + query : n_tot - 1;  // last token this lane's query sees
 
-    u32x4 kf[KF], vf[2 * DB];
-    {
-        const u32x4 *kp = kfrag(t_begin);
+    // Ring of D blocks of keys and values in flight (32 registers per slot at HD = 64, 64 at HD = 128): a wavefront
+    // with at most D blocks (short contexts split over the wavefronts of a workgroup) requests all of them at once
+    // and pays the memory latency once.
+    u32x4 kf[D][KF], vf[D][2 * DB];
+    const int n_blk = (t_end - t_begin + t_stride - 1) / t_stride;
+    auto load_k = [&](int s, int b) {
+        const u32x4 *kp = kfrag(t_begin + b * t_stride);
 #pragma unroll
-        for (int kb = 0; kb < KF; ++kb) kf[kb] = kp[kb * 64];
-        const u32x4 *vp = vfrag(t_begin);
+        for (int kb = 0; kb < KF; ++kb) kf[s][kb] = kp[kb * 64];
+    };
+    auto load_v = [&](int s, int b) {
+        const u32x4 *vp = vfrag(t_begin + b * t_stride);
 #pragma unroll
-        for (int f = 0; f < 2 * DB; ++f) vf[f] = vp[f * 64];
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    for (int t0 = t_begin; t0 < t_end; t0 += t_stride) {
-        f32x16 s;
+        for (int f = 0; f < 2 * DB; ++f) vf[s][f] = vp[f * 64];
+    };
+    // one block: scores, online softmax, O += V P; `next` >= 0: block to request into the slot as soon as its
+    // keys (after the scores) and values (after the PV product) have been consumed
+    auto block = [&](int s, int b, int next) {
+        const int t0 = t_begin + b * t_stride;
+        f32x16 sc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+        for (int v = 0; v < 16; ++v) sc[v] = 0.0f;
 #pragma unroll
         for (int kb = 0; kb < KF; ++kb)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kb]), __builtin_bit_cast(bf16x8, qf[kb]), s, 0, 0, 0);
-        // next block's keys while this block's softmax and PV run (clamped to the last block: a cache hit)
-        const int tn = t0 + t_stride < t_end ? t0 + t_stride : t0;
-        {
-            const u32x4 *kp = kfrag(tn);
-#pragma unroll
-            for (int kb = 0; kb < KF; ++kb) kf[kb] = kp[kb * 64];
-        }
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s][kb]), __builtin_bit_cast(bf16x8, qf[kb]), sc, 0, 0, 0);
+        if (next >= 0) load_k(s, next);
         __builtin_amdgcn_sched_barrier(0);
-        // scores -> base-2 logits, causal / length mask
+        // The softmax arithmetic below is what bounds a short-context workgroup (all of a head's blocks run on one
+        // CU), so it is kept lean and branch-free: one compare per score for the causal / length mask, raw
+        // v_exp_f32 (arguments <= 0; results below 2^-126 may flush to 0), hardware pair conversion to bf16 (round
+        // to nearest even).
+        {
+            const int tb = t0 + 4 * (lane >> 5) - last_vis;  // token of accumulator register v is visible iff tb + 8 (v / 4) + v % 4 <= 0
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[v] = tb <= -(8 * (v >> 2) + (v & 3)) ? sc[v] : -INFINITY;
+        }
         float mx = -INFINITY;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int tok = t0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const bool vis = tok <= kv + query && tok < n_tot;
-            s[v] = vis ? s[v] * a.scale_log2e : -INFINITY;
-            mx = fmaxf(mx, s[v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * a.scale_log2e;  // base-2 logits from here on
         const float m_new = fmaxf(m_run, mx);
         // a query with nothing visible so far keeps m = -inf; avoid (-inf) - (-inf)
         const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = exp2f(m_run - m_use);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
         float psum = 0.0f;
         uint32_t pk[8];
 #pragma unroll
         for (int v = 0; v < 16; v += 2) {
-            const float p0 = exp2f(s[v] - m_use), p1 = exp2f(s[v + 1] - m_use);
-            const bf16_t b0 = float_to_bf16(p0), b1 = float_to_bf16(p1);
-            psum += bf16_to_float(b0) + bf16_to_float(b1);  // the sum of what is actually multiplied
-            pk[v >> 1] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            const f32x2_t pp = {__builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2e, -m_use)),
+                                __builtin_amdgcn_exp2f(fmaf(sc[v + 1], a.scale_log2e, -m_use))};
+            const uint32_t u = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, hw_bf16x2_t));
+            // the sum of what is actually multiplied
+            psum += __builtin_bit_cast(float, u << 16) + __builtin_bit_cast(float, u & 0xFFFF0000u);
+            pk[v >> 1] = u;
         }
         l_run = l_run * alpha + psum;
         m_run = m_new;
@@ -213,16 +227,30 @@ SJD_D void attention_wave(const AttnArgs &a, int seg, int h, int kvh, int qt, in
         const u32x4 p0 = {pk[0], pk[1], pk[2], pk[3]}, p1 = {pk[4], pk[5], pk[6], pk[7]};
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[db]), __builtin_bit_cast(bf16x8, p0), o[db], 0, 0, 0);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[DB + db]), __builtin_bit_cast(bf16x8, p1), o[db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[s][db]), __builtin_bit_cast(bf16x8, p0), o[db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[s][DB + db]), __builtin_bit_cast(bf16x8, p1), o[db], 0, 0, 0);
         }
-        {
-            const u32x4 *vp = vfrag(tn);
-#pragma unroll
-            for (int f = 0; f < 2 * DB; ++f) vf[f] = vp[f * 64];
-        }
+        if (next >= 0) load_v(s, next);
         __builtin_amdgcn_sched_barrier(0);
+    };
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (s < n_blk) {
+            load_k(s, s);
+            load_v(s, s);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    int b0 = 0;
+    for (; b0 + 2 * D <= n_blk; b0 += D) {  // every refill of these groups is a block that exists: branch-free body
+#pragma unroll
+        for (int s = 0; s < D; ++s) block(s, b0 + s, b0 + s + D);
     }
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (b0 + s < n_blk) block(s, b0 + s, b0 + s + D < n_blk ? b0 + s + D : -1);
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (b0 + D + s < n_blk) block(s, b0 + D + s, -1);
 }
 
 template <int HD>
@@ -242,7 +270,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
     const int t_end = t_begin + a.chunk < n_vis ? t_begin + a.chunk : n_vis;
     f32x16 o[DB];
     float m_run, l_run;
-    attention_wave<HD>(a, seg, h, kvh, qt, t_begin, t_end, 32, kv, n_tot, lane, o, m_run, l_run);
+    attention_wave<HD, (HD <= 64 ? 3 : 2)>(a, seg, h, kvh, qt, t_begin, t_end, 32, kv, n_tot, lane, o, m_run, l_run);
     const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
     const size_t slot = (((size_t)seg * a.H + h) * a.n_qt + qt) * a.n_chunks + c;
@@ -273,9 +301,16 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
     const int kv = a.seg_kv[seg];
     const int n_tot = n_act > 0 ? kv + n_act : 0;
     const int n_vis = 32 * qt < n_act ? min(n_tot, kv + 32 * (qt + 1)) : 0;  // nothing later is visible to this query tile
+#ifdef SJD_PHASE_TIMING
+#define SJD_ATTN_STAMP(i) do { if (a.phase && threadIdx.x == 0) a.phase[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SJD_ATTN_STAMP(i) do { } while (0)
+#endif
+    SJD_ATTN_STAMP(0);
     f32x16 o[DB];
     float m_run, l_run;
-    attention_wave<HD>(a, seg, h, kvh, qt, 32 * wave, n_vis, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
+    attention_wave<HD, (HD <= 64 ? 3 : 1)>(a, seg, h, kvh, qt, 32 * wave, n_vis, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
+    SJD_ATTN_STAMP(1);
     const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
 
@@ -298,6 +333,7 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
     const bool row = 32 * qt + query < a.L;
     const bool active = row && a.row_tok[m] >= 0 && denom > 0.0f;
     const float inv = active ? 1.0f / denom : 0.0f;
+    SJD_ATTN_STAMP(2);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
         __syncthreads();
@@ -318,6 +354,7 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
             }
         }
     }
+    SJD_ATTN_STAMP(3);
 }
 
 // Merges the chunks of every (row, head): out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.

@@ -65,6 +65,13 @@ struct SkinnyArgs {
     uint32_t pf_slab_bytes;
     int pf_groups, pf_wgs;   // pf_wgs: a multiple of 8, 0 = none
     uint32_t *pf_sink;       // a device word nobody reads; a (practically never taken) store to it keeps the loads alive
+    // ... and of the keys and values that the next attention launch will read (workgroups [groups + pf_wgs,
+    // groups + pf_wgs + kv_wgs)): the complete pages of the context before this forward's rows, which no launch of
+    // this forward writes.  Attention workgroup p = (segment p / H, head p % H) runs on XCD p % 8.
+    int kv_wgs;                 // a multiple of 8, 0 = none
+    KvPool kv_pool;             // the pools of the layer whose attention comes next
+    int kv_pairs;               // segments * H
+    const int32_t *kv_seg_kv;   // [segments] tokens in the cache before this forward's rows
 #ifdef SJD_PHASE_TIMING
     unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
 #endif
@@ -170,12 +177,37 @@ SJD_D void l2_warm_next(const SkinnyArgs &a, int id, int first_id, int tid, int 
     if (sink == 0x9e3779b9u) *a.pf_sink = sink;  // a word nobody reads; the store only keeps the loads alive
 }
 
+SJD_D void l2_warm_kv(const SkinnyArgs &a, int id, int first_id, int tid, int threads) {
+    const int xcd = id & 7, rank = (id - first_id) >> 3, ranks = a.kv_wgs >> 3;
+    const int G = a.H / a.Hkv;
+    const size_t blk_bytes = (size_t)a.kv_pool.page_tokens * a.hd * sizeof(bf16_t);  // one (page, kv head) block of keys or values
+    const uint32_t blk_lines = (uint32_t)(blk_bytes >> 7), pair_lines = (uint32_t)a.kv_pool.pages_per_seg * 2 * blk_lines;
+    const uint32_t n_pairs = a.kv_pairs > xcd ? (uint32_t)(a.kv_pairs - xcd + 7) >> 3 : 0;  // this XCD's (segment, head) pairs
+    uint32_t sink = 0;
+    // One flat index space over (pair, page, keys | values, line), so that a thread's few lines are independent of
+    // each other: the page count of the segment and the page table entry load side by side, then the line.
+#pragma unroll 2
+    for (uint32_t i = rank * threads + tid; i < n_pairs * pair_lines; i += ranks * threads) {
+        const uint32_t j = i / pair_lines, r0 = i - j * pair_lines;
+        const uint32_t pg = r0 / (2 * blk_lines), r = r0 - pg * 2 * blk_lines;
+        const int p = xcd + 8 * (int)j, seg = p / a.H, kvh = (p % a.H) / G;
+        const int pages = a.kv_seg_kv[seg] / a.kv_pool.page_tokens;
+        const int page = a.kv_pool.page_table[seg * a.kv_pool.pages_per_seg + pg];
+        if ((int)pg < pages) {
+            const char *base = r < blk_lines ? (const char *)a.kv_pool.k : (const char *)a.kv_pool.v;
+            sink ^= *reinterpret_cast<const uint32_t *>(base + ((size_t)page * a.Hkv + kvh) * blk_bytes + (size_t)(r % blk_lines) * 128);
+        }
+    }
+    if (sink == 0x9e3779b9u) *a.pf_sink = sink;
+}
+
 template <int MT, int NBW, int NW, int DEPTH, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
-    if (a.pf_wgs > 0 && (int)blockIdx.x >= a.groups) {  // whole workgroup: only touches the next launch's weights
-        l2_warm_next(a, blockIdx.x, a.groups, tid, NW * 64);
+    if ((int)blockIdx.x >= a.groups && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
+        if ((int)blockIdx.x < a.groups + a.pf_wgs) l2_warm_next(a, blockIdx.x, a.groups, tid, NW * 64);
+        else l2_warm_kv(a, blockIdx.x, a.groups + a.pf_wgs, tid, NW * 64);
         return;
     }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
@@ -473,8 +505,8 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     constexpr int DEPTH = SJD_SKINNY_DEPTH;
     SkinnyArgs a = a_in;
     a.groups = groups;
-    if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = 0;
-    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1) + a.pf_wgs, a.ksplit);
+    if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = a.kv_wgs = 0;
+    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1) + a.pf_wgs + a.kv_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);

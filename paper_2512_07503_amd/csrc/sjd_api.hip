@@ -355,8 +355,21 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         if (wgs < 8 || fit < 1) return;
         a.pf_base = (const char *)nx.W; a.pf_slab_bytes = slab; a.pf_groups = fit; a.pf_wgs = wgs; a.pf_sink = c->pf_sink;
     };
+    // The same for the keys and values of the next one-pass attention launch (one workgroup per (head, segment), in
+    // that order); call after warm(): takes what is left of the 256 CUs.
+    auto warm_kv = [&](int cur_groups, const KvPool &pool) {
+        a.kv_wgs = 0;
+        if (!c->l2_warm || tile || m_groups > 1 || !c->attn_mfma || !c->attn_onepass || c->L > 32) return;
+        const size_t kv_bytes = (size_t)(M / c->L) * Hkv * md.max_ctx * hd * 2 * sizeof(bf16_t);
+        const int room = (256 - cur_groups - a.pf_wgs) / 8 * 8;
+        a.kv_wgs = std::max(0, std::min(room, (int)((kv_bytes / (48 << 10) + 7) / 8 * 8)));
+        a.kv_pairs = (M / c->L) * H;
+        a.kv_seg_kv = c->rm.seg_kv;
+        a.kv_pool = pool;
+        a.pf_sink = c->pf_sink;
+    };
     const Proj none = {nullptr, 0, 0, 0, false};
-    auto resid = [&](int cls, const void *A, const void *W, int K, const Proj &nx) -> int {
+    auto resid = [&](int cls, const void *A, const void *W, int K, const Proj &nx, const KvPool *kv_next) -> int {
         a.A = (const bf16_t *)A; a.W = (const bf16_t *)W; a.KB = K / 16; a.N = d;
         a.pf_wgs = 0;
         if (tile) {
@@ -387,8 +400,9 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         if (ks == 1) {
             whole_k();
             warm(groups, nx);
+            if (kv_next) warm_kv(groups, *kv_next);
             SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
-            a.pf_wgs = 0;
+            a.pf_wgs = a.kv_wgs = 0;
             return SJD_OK;
         }
         a.kb_per_split = ceil_div(a.KB, ks);
@@ -417,11 +431,12 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         } else {
             whole_k();
             warm(groups_qkv, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
+            if (l == 0) warm_kv(groups_qkv, pool);  // later layers: requested by the down projection before them
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, groups_qkv, 2, nw_for(groups_qkv)));
-            a.pf_wgs = 0;
+            a.pf_wgs = a.kv_wgs = 0;
         }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
-        { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd, Proj{lw.wgu, F / 32, 2, d / 16, true}); if (rc) return rc; }
+        { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd, Proj{lw.wgu, F / 32, 2, d / 16, true}, nullptr); if (rc) return rc; }
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
         if (tile) {
             whole_k();
@@ -435,7 +450,10 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         const Proj after_down = l + 1 < md.n_layers ? Proj{c->layers[l + 1].wqkv, groups_qkv, 2, d / 16, true}
                                 : with_head         ? Proj{c->lm_head, ceil_div(ceil_div(c->Vs, 32), 2), 2, d / 16, true}
                                                     : none;
-        { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F, after_down); if (rc) return rc; }
+        KvPool pool_next = pool;
+        pool_next.k = (char *)c->kpool + c->pool_layer_bytes * (l + 1);
+        pool_next.v = (char *)c->vpool + c->pool_layer_bytes * (l + 1);
+        { int rc = resid(KC_GEMM_DOWN, c->h, lw.wdown, F, after_down, l + 1 < md.n_layers ? &pool_next : nullptr); if (rc) return rc; }
     }
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
