@@ -58,8 +58,11 @@ enum {
     SJD_ATTENTION_CHUNKED = 8, /* bf16: always split the context over workgroups and merge
                                 * in a second kernel, also where one workgroup per head
                                 * would do (short contexts)                            */
-    SJD_KERNELS_TILES = 16     /* bf16, >= 256 rows: the tile kernels also for models too
+    SJD_KERNELS_TILES = 16,    /* bf16, >= 256 rows: the tile kernels also for models too
                                 * narrow to fill the chip with 256 x 128 tiles         */
+    SJD_NO_L2_WARM = 32        /* bf16, <= 64 rows: projection launches carry no extra
+                                * workgroups that touch the next launch's weights and
+                                * key/value pages into L2 (same results either way)    */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

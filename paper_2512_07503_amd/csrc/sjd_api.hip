@@ -613,7 +613,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         if ((rc = dev_alloc(c, &c->pf_sink, 256))) return rc;
         if ((rc = dev_alloc(c, &c->row_meta, (size_t)M * sizeof(QkvRow)))) return rc;
         if ((rc = dev_alloc(c, &c->row_rot, (size_t)M * (hd / 2) * sizeof(float2)))) return rc;
-        if (const char *e = getenv("SJD_L2_WARM")) c->l2_warm = atoi(e) != 0;
+        c->l2_warm = !(md.kernel_flags & SJD_NO_L2_WARM);
     }
     if (c->attn_mfma) {
         // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
