@@ -328,10 +328,11 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     a.part = c->skinny_part;
     auto whole_k = [&]() { a.ksplit = 1; a.kb_per_split = a.KB; };
     auto no_room = [&]() { sjd_set_error(c->err, "split-K workspace too small"); return SJD_EINVAL; };
-    // measured (cold weights): from about 50 column groups on, 4 wavefronts with the same ring depth stream a
-    // workgroup's share faster than 8 (the second wavefront of a SIMD only queues behind the first) and halve the
-    // LDS reduction; with fewer groups 8 wavefronts are needed to keep enough loads in flight per CU
-    auto nw_for = [](int groups) { return groups >= 50 ? 4 : 8; };
+    // Wavefronts per workgroup, measured: 8 pull a workgroup's share through the CU's L1 faster than 4 and halve
+    // the epilogue's elements per thread; once a launch fills most CUs with weights that come from HBM (the 7B
+    // shapes' gate/up and head) a CU's outstanding misses are the limit either way, the second wavefront of a SIMD
+    // only queues behind the first, and 4 win by the cheaper LDS reduction.
+    auto nw_for = [](int groups) { return groups >= 200 ? 4 : 8; };
     // many rows: LDS-staged 256 x 128 tiles (the projections are a dense contraction there, not a weight stream)
     // ... provided the model is wide enough for 256 x 128 tiles to fill the chip (QKV: >= 96 tiles); a narrow model
     // with a long window keeps the row-group kernels, which give it more workgroups
