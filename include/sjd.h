@@ -178,6 +178,30 @@ int sjd_debug_copy_logits(sjd_ctx *ctx, float *dst_host);
  * the forward: the KV cache is not written, its length advances as usual. */
 int sjd_debug_step_from_logits(sjd_ctx *ctx, const float *logits_host, sjd_step_result *out);
 
+/* Snapshot of the decoding state of the current batch, to HOST memory and back.
+ * What Sec. 4.1 carries from one iteration to the next is small and explicit:
+ * the accepted tokens, the window's drafts with the distributions they were
+ * drawn from (the previous iteration's rows), the step counter that indexes the
+ * random stream, and the cache of the accepted prefix.  A snapshot holds exactly
+ * that (cache pages of accepted positions only), so a half-decoded batch can be
+ * parked and resumed, or rolled back: after sjd_snapshot_restore the following
+ * sjd_step calls return what they returned after sjd_snapshot_save, bit for bit.
+ *   sjd_snapshot_size     *bytes = size a save would write now (it grows with
+ *                         the accepted prefix).
+ *   sjd_snapshot_save     writes the snapshot to dst_host (cap bytes available);
+ *                         *written = its size.  SJD_ECAPACITY if cap is too small.
+ *   sjd_snapshot_restore  src_host / bytes as written by a save on a context
+ *                         created with the same model description and sampling
+ *                         parameters (anything else, a truncated or altered
+ *                         buffer: SJD_EINVAL, context unchanged).  Replaces
+ *                         whatever batch the context held; no prefill needed.
+ * All three return after the copies completed; SJD_ESTATE before the first
+ * prefill (size, save).  The buffer is plain bytes owned by the caller; its
+ * format is private to the library version that wrote it. */
+int sjd_snapshot_size(sjd_ctx *ctx, uint64_t *bytes);
+int sjd_snapshot_save(sjd_ctx *ctx, void *dst_host, uint64_t cap, uint64_t *written);
+int sjd_snapshot_restore(sjd_ctx *ctx, const void *src_host, uint64_t bytes);
+
 /* Per-kernel timing.  With tracing on, sjd_step brackets every kernel launch
  * with HIP events on the context's stream and accumulates their durations.
  * sjd_trace_read copies up to cap entries: name (static string), number of

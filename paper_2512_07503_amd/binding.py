@@ -70,6 +70,9 @@ def lib():
         L.sjd_last_error.restype = C.c_char_p
         L.sjd_debug_copy_logits.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.sjd_debug_step_from_logits.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(StepResult)]
+        L.sjd_snapshot_size.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
+        L.sjd_snapshot_save.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64)]
+        L.sjd_snapshot_restore.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.sjd_trace_enable.argtypes = [C.c_void_p, C.c_int32]
         L.sjd_trace_reset.argtypes = [C.c_void_p]
         L.sjd_trace_read.argtypes = [C.c_void_p, C.POINTER(TraceEntry), C.c_int32, IP]
@@ -200,6 +203,21 @@ class Decoder:
         toks, refs, n = np.zeros(self.L, dtype=np.int32), np.zeros(self.L, dtype=np.int32), C.c_int32(0)
         _check(lib().sjd_get_window(self.ctx, seq, toks.ctypes.data_as(IP), refs.ctypes.data_as(IP), C.byref(n)), self.ctx)
         return toks, refs, n.value
+
+    def snapshot(self):
+        """The decoding state of the current batch as a uint8 array (sjd_snapshot_size + sjd_snapshot_save)."""
+        n = C.c_uint64(0)
+        _check(lib().sjd_snapshot_size(self.ctx, C.byref(n)), self.ctx)
+        buf = np.zeros(n.value, dtype=np.uint8)
+        w = C.c_uint64(0)
+        _check(lib().sjd_snapshot_save(self.ctx, buf.ctypes.data_as(C.c_void_p), n.value, C.byref(w)), self.ctx)
+        return buf[:w.value]
+
+    def restore(self, buf):
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        _check(lib().sjd_snapshot_restore(self.ctx, buf.ctypes.data_as(C.c_void_p), buf.size), self.ctx)
+        # the batch size travels with the snapshot
+        self.n_seqs = int(np.frombuffer(buf[:32].tobytes(), dtype=np.int32)[5])
 
     def decode(self, max_steps=1 << 30):
         hist = []

@@ -62,7 +62,6 @@ struct sjd_ctx {
     hipStream_t stream = nullptr;
     char err[512] = "";
     int hd = 0, Vs = 0, L = 0, S = 0, n_seqs = 0, pt = 0, pps = 0, n_pages = 0, max_visible = 0;
-    size_t esize = 0;
     bool prefilled = false, all_done = false;
     // one sjd_step = the same launch sequence with the same arguments every time (what changes lives in device
     // memory): captured once per batch size into a HIP graph and replayed
@@ -90,6 +89,7 @@ struct sjd_ctx {
     void *kpool = nullptr, *vpool = nullptr;
     size_t pool_layer_bytes = 0;
     int32_t *page_table = nullptr;
+    std::vector<int32_t> page_table_host;  // what sjd_prefill uploaded (snapshots carry it)
     // workspaces
     float *x = nullptr, *partial = nullptr, *logits = nullptr;
     void *xn = nullptr, *q = nullptr, *attn = nullptr, *h = nullptr;
@@ -884,6 +884,7 @@ int sjd_prefill(sjd_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, cons
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->n_image_dev, n_image_tokens, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->page_table, table.data(), table.size() * 4, hipMemcpyHostToDevice, st));
     SJD_HIP_TRY(c->err, hipStreamSynchronize(st));  // the host staging vectors may go away on an early return
+    c->page_table_host = table;
     const int chunks = ceil_div(max_prompt - 1, L);
     for (int ch = 0; ch < chunks; ++ch) {
         SJD_LAUNCH(c, KC_STAGE, launch_stage_prompt(st, c->rm, c->prompt_dev, c->prompt_len_dev, max_prompt, ch, L, n_seqs));
@@ -990,6 +991,181 @@ int sjd_trace_read(sjd_ctx *c, sjd_trace_entry *dst, int32_t cap, int32_t *n_out
         dst[i].total_ms = c->tracer.total_ms[i];
     }
     *n_out = KC_COUNT;
+    return SJD_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------ snapshots
+// The state that Sec. 4.1 carries from one iteration to the next: the accepted tokens, the window's drafts with the
+// rows they were drawn from (the previous iteration's distributions), and the cache of the accepted prefix.
+namespace {
+
+struct SnapshotHeader {
+    uint64_t magic, total_bytes;
+    int32_t version, n_seqs, all_done;
+    // the context a snapshot fits: same model, capacities and sampling set-up
+    int32_t n_layers, d_model, n_heads, n_kv_heads, hd, Vs, L, S, max_ctx, pt, pps, dtype, init_mode, row_width;
+    uint64_t seed;
+    float cfg_scale, temperature, reuse_tau;
+    int32_t top_k;
+    int32_t pages_used[1];  // [n_seqs * 2] follows (flexible; the struct is written with its real length)
+};
+constexpr uint64_t kSnapshotMagic = 0x31544e53444a53ull;  // "SJDSNT1"
+
+// the per-sequence device arrays of the decoding state: pointer, bytes per sequence
+struct StateArray { void *p; size_t per_seq; };
+std::vector<StateArray> state_arrays(sjd_ctx *c) {
+    const DecideState &d = c->ds;
+    const size_t L = c->L, V = c->Vs;
+    std::vector<StateArray> a = {
+        {d.win_tok, L * 4}, {d.anchor, 8}, {d.ref_row, L * 4}, {d.n_img, 4}, {d.n_image, 4}, {d.kv_len, 8}, {d.Le, 4},
+        {d.out_tok, (size_t)d.max_img * 4}, {d.acc_len, 4}, {d.cand, L * 4}, {d.cand_new, L * 4},
+        {d.e_buf[0], L * V * 4}, {d.e_buf[1], L * V * 4}, {d.Z_buf[0], L * 8}, {d.Z_buf[1], L * 8}, {d.res, sizeof(sjd_step_result)}};
+    if (c->sp.init_mode == 4) {
+        a.push_back({d.hist_e, (size_t)c->sp.row_width * V * 4});
+        a.push_back({d.hist_Z, (size_t)c->sp.row_width * 8});
+    }
+    return a;
+}
+size_t snapshot_header_bytes(int n_seqs) { return (sizeof(SnapshotHeader) + (size_t)(2 * n_seqs) * 4 + 15) / 16 * 16; }
+
+// pages in use per segment (committed positions only: the window's entries are rewritten by every step)
+int snapshot_pages(sjd_ctx *c, std::vector<int32_t> &pages) {
+    std::vector<int32_t> kv((size_t)c->n_seqs * 2);
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    SJD_HIP_TRY(c->err, hipMemcpy(kv.data(), c->ds.kv_len, kv.size() * 4, hipMemcpyDeviceToHost));
+    pages.resize(kv.size());
+    for (size_t i = 0; i < kv.size(); ++i) pages[i] = ceil_div(kv[i], c->pt);
+    return SJD_OK;
+}
+size_t snapshot_bytes(sjd_ctx *c, int n_seqs, const std::vector<int32_t> &pages) {
+    size_t n = snapshot_header_bytes(n_seqs) + (size_t)c->S * 2 * c->pps * 4 + 16 /* step counter */;
+    for (const StateArray &a : state_arrays(c)) n += a.per_seq * n_seqs;
+    size_t total_pages = 0;
+    for (int32_t p : pages) total_pages += p;
+    const size_t page_bytes = c->pool_layer_bytes / c->n_pages;  // one page of one layer's key (or value) pool, all kv heads
+    return n + total_pages * page_bytes * 2 * c->md.n_layers;
+}
+bool snapshot_fits(const sjd_ctx *c, const SnapshotHeader &h) {
+    return h.n_layers == c->md.n_layers && h.d_model == c->md.d_model && h.n_heads == c->md.n_heads &&
+           h.n_kv_heads == c->md.n_kv_heads && h.hd == c->hd && h.Vs == c->Vs && h.L == c->L && h.S == c->S &&
+           h.max_ctx == c->md.max_ctx && h.pt == c->pt && h.pps == c->pps && h.dtype == c->md.dtype &&
+           h.init_mode == c->sp.init_mode && h.row_width == c->sp.row_width && h.seed == c->sp.seed &&
+           h.cfg_scale == c->sampling.cfg_scale && h.temperature == c->sampling.temperature &&
+           (h.reuse_tau == c->sampling.reuse_tau || (h.reuse_tau != h.reuse_tau && c->sampling.reuse_tau != c->sampling.reuse_tau)) &&
+           h.top_k == c->sampling.top_k;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sjd_snapshot_size(sjd_ctx *c, uint64_t *bytes) {
+    if (!c || !bytes) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "no prefill yet"); return SJD_ESTATE; }
+    std::vector<int32_t> pages;
+    int rc = snapshot_pages(c, pages);
+    if (rc) return rc;
+    *bytes = snapshot_bytes(c, c->n_seqs, pages);
+    return SJD_OK;
+}
+
+int sjd_snapshot_save(sjd_ctx *c, void *dst_host, uint64_t cap, uint64_t *written) {
+    if (!c || !dst_host || !written) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "no prefill yet"); return SJD_ESTATE; }
+    std::vector<int32_t> pages;
+    int rc = snapshot_pages(c, pages);
+    if (rc) return rc;
+    const size_t total = snapshot_bytes(c, c->n_seqs, pages);
+    if (cap < total) { sjd_set_error(c->err, "snapshot needs %zu bytes, buffer has %llu", total, (unsigned long long)cap); return SJD_ECAPACITY; }
+    char *w = (char *)dst_host;
+    const size_t hb = snapshot_header_bytes(c->n_seqs);
+    memset(w, 0, hb);
+    SnapshotHeader *h = (SnapshotHeader *)w;
+    h->magic = kSnapshotMagic; h->total_bytes = total; h->version = 1; h->n_seqs = c->n_seqs; h->all_done = c->all_done;
+    h->n_layers = c->md.n_layers; h->d_model = c->md.d_model; h->n_heads = c->md.n_heads; h->n_kv_heads = c->md.n_kv_heads;
+    h->hd = c->hd; h->Vs = c->Vs; h->L = c->L; h->S = c->S; h->max_ctx = c->md.max_ctx; h->pt = c->pt; h->pps = c->pps;
+    h->dtype = c->md.dtype; h->init_mode = c->sp.init_mode; h->row_width = c->sp.row_width; h->seed = c->sp.seed;
+    h->cfg_scale = c->sampling.cfg_scale; h->temperature = c->sampling.temperature; h->reuse_tau = c->sampling.reuse_tau;
+    h->top_k = c->sampling.top_k;
+    memcpy(h->pages_used, pages.data(), pages.size() * 4);
+    w += hb;
+    memcpy(w, c->page_table_host.data(), c->page_table_host.size() * 4);
+    w += c->page_table_host.size() * 4;
+    SJD_HIP_TRY(c->err, hipMemcpy(w, c->ds.step, 4, hipMemcpyDeviceToHost));
+    w += 16;
+    for (const StateArray &a : state_arrays(c)) {
+        SJD_HIP_TRY(c->err, hipMemcpy(w, a.p, a.per_seq * c->n_seqs, hipMemcpyDeviceToHost));
+        w += a.per_seq * c->n_seqs;
+    }
+    const size_t page_bytes = c->pool_layer_bytes / c->n_pages;  // one page of one layer's key (or value) pool, all kv heads
+    for (int l = 0; l < c->md.n_layers; ++l)
+        for (int kv = 0; kv < 2; ++kv) {
+            const char *pool = (const char *)(kv ? c->vpool : c->kpool) + c->pool_layer_bytes * l;
+            for (int seg = 0; seg < c->n_seqs * 2; ++seg)
+                for (int i = 0; i < pages[seg]; ++i) {
+                    const int page = c->page_table_host[(size_t)seg * c->pps + i];
+                    SJD_HIP_TRY(c->err, hipMemcpyAsync(w, pool + (size_t)page * page_bytes, page_bytes, hipMemcpyDeviceToHost, c->stream));
+                    w += page_bytes;
+                }
+        }
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    *written = (uint64_t)(w - (char *)dst_host);
+    return SJD_OK;
+}
+
+int sjd_snapshot_restore(sjd_ctx *c, const void *src_host, uint64_t bytes) {
+    if (!c || !src_host) return SJD_EINVAL;
+    if (bytes < sizeof(SnapshotHeader)) { sjd_set_error(c->err, "snapshot truncated"); return SJD_EINVAL; }
+    const SnapshotHeader *h = (const SnapshotHeader *)src_host;
+    if (h->magic != kSnapshotMagic || h->version != 1) { sjd_set_error(c->err, "not a snapshot of this library version"); return SJD_EINVAL; }
+    if (!snapshot_fits(c, *h)) { sjd_set_error(c->err, "snapshot was taken from a context with another model, capacity or sampling set-up"); return SJD_EINVAL; }
+    if (h->n_seqs < 1 || h->n_seqs > c->S || h->total_bytes != bytes) { sjd_set_error(c->err, "snapshot truncated or corrupt"); return SJD_EINVAL; }
+    const int n_seqs = h->n_seqs;
+    std::vector<int32_t> pages(h->pages_used, h->pages_used + 2 * n_seqs);
+    for (int32_t p : pages)
+        if (p < 0 || p > c->pps) { sjd_set_error(c->err, "snapshot corrupt (page count)"); return SJD_EINVAL; }
+    if (bytes < snapshot_header_bytes(n_seqs) || snapshot_bytes(c, n_seqs, pages) != bytes) {
+        sjd_set_error(c->err, "snapshot truncated or corrupt");
+        return SJD_EINVAL;
+    }
+    const char *r = (const char *)src_host + snapshot_header_bytes(n_seqs);
+    const size_t table_n = (size_t)c->S * 2 * c->pps;
+    std::vector<int32_t> table((const int32_t *)r, (const int32_t *)r + table_n);
+    for (int seg = 0; seg < n_seqs * 2; ++seg)
+        for (int i = 0; i < pages[seg]; ++i)
+            if (table[(size_t)seg * c->pps + i] < 0 || table[(size_t)seg * c->pps + i] >= c->n_pages) {
+                sjd_set_error(c->err, "snapshot corrupt (page table)");
+                return SJD_EINVAL;
+            }
+    // everything checked: from here on the context's batch is replaced
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    c->prefilled = false;
+    c->n_seqs = n_seqs;
+    c->page_table_host = table;
+    SJD_HIP_TRY(c->err, hipMemcpy(c->page_table, table.data(), table_n * 4, hipMemcpyHostToDevice));
+    r += table_n * 4;
+    SJD_HIP_TRY(c->err, hipMemcpy(c->ds.step, r, 4, hipMemcpyHostToDevice));
+    r += 16;
+    for (const StateArray &a : state_arrays(c)) {
+        SJD_HIP_TRY(c->err, hipMemcpy(a.p, r, a.per_seq * n_seqs, hipMemcpyHostToDevice));
+        r += a.per_seq * n_seqs;
+    }
+    const size_t page_bytes = c->pool_layer_bytes / c->n_pages;  // one page of one layer's key (or value) pool, all kv heads
+    for (int l = 0; l < c->md.n_layers; ++l)
+        for (int kv = 0; kv < 2; ++kv) {
+            char *pool = (char *)(kv ? c->vpool : c->kpool) + c->pool_layer_bytes * l;
+            for (int seg = 0; seg < n_seqs * 2; ++seg)
+                for (int i = 0; i < pages[seg]; ++i) {
+                    const int page = table[(size_t)seg * c->pps + i];
+                    SJD_HIP_TRY(c->err, hipMemcpyAsync(pool + (size_t)page * page_bytes, r, page_bytes, hipMemcpyHostToDevice, c->stream));
+                    r += page_bytes;
+                }
+        }
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    c->all_done = h->all_done != 0;
+    c->prefilled = true;
     return SJD_OK;
 }
 
