@@ -60,9 +60,12 @@ enum {
                                 * would do (short contexts)                            */
     SJD_KERNELS_TILES = 16,    /* bf16, >= 256 rows: the tile kernels also for models too
                                 * narrow to fill the chip with 256 x 128 tiles         */
-    SJD_NO_L2_WARM = 32        /* bf16, <= 64 rows: projection launches carry no extra
+    SJD_NO_L2_WARM = 32,       /* bf16, <= 64 rows: projection launches carry no extra
                                 * workgroups that touch the next launch's weights and
                                 * key/value pages into L2 (same results either way)    */
+    SJD_TILES_256_ROWS = 64    /* bf16, >= 256 rows: every tile kernel launch uses 256-row
+                                * workgroup tiles (default: 128-row tiles where they
+                                * balance the CUs better)                              */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

@@ -44,6 +44,10 @@ struct SkinnyArgs {
     float *x;          // [M][N] fp32 residual stream, updated in place
     bf16_t *xb;        // the same in bf16, fragment-major [M][N]
     int N;             // also the logits row length for HEAD
+    // Many-row kernels: per-row sums of squares of the (bf16) input rows, as row_ssq_n partial sums per row written
+    // by the kernel that produced the rows; NULL: taken from the activation fragments inside the k-loop
+    const float *row_ssq_part;
+    int row_ssq_n;
     // QKV: per-row tables written once per forward by embed_dual_kernel (no dependent loads in the projections)
     const QkvRow *row_meta;   // [M]
     const float2 *row_rot;    // [M][hd / 2] (cos, sin) of the row's position; (1, 0) for rows that are not computed
@@ -421,6 +425,8 @@ struct RowTables {
     int pages_per_seg, page_tokens, L, H, hd;
     QkvRow *meta;
     float2 *rot;
+    float *ssq_part;   // [M][ssq_n] sum of squares of the row in slot 0, zeros in the others (may be NULL)
+    int ssq_n;
 };
 __global__ void embed_dual_kernel(const bf16_t *__restrict__ emb, const int32_t *__restrict__ row_tok, float *__restrict__ x,
                                   bf16_t *__restrict__ xb, int d, RowTables t) {
@@ -444,10 +450,18 @@ __global__ void embed_dual_kernel(const bf16_t *__restrict__ emb, const int32_t 
     for (int j = threadIdx.x; j < half; j += blockDim.x)
         t.rot[(size_t)m * half + j] = pos >= 0 ? make_float2(t.rope_cos[(size_t)pos * half + j], t.rope_sin[(size_t)pos * half + j])
                                                : make_float2(1.0f, 0.0f);
+    float sq = 0.0f;
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
         const bf16_t v = tok >= 0 ? emb[(size_t)tok * d + i] : (bf16_t)0;
-        x[(size_t)m * d + i] = bf16_to_float(v);
+        const float f = bf16_to_float(v);
+        x[(size_t)m * d + i] = f;
         xb[Layout<bf16_t>::a_index(m, i, d)] = v;
+        sq = fmaf(f, f, sq);
+    }
+    if (t.ssq_part) {
+        __shared__ float scratch[17];
+        const float total = block_sum_f32(sq, scratch);
+        for (int c = threadIdx.x; c < t.ssq_n; c += blockDim.x) t.ssq_part[(size_t)m * t.ssq_n + c] = c == 0 ? total : 0.0f;
     }
 }
 
@@ -487,14 +501,25 @@ __global__ void pack_weight_fused_kernel(const bf16_t *__restrict__ s0, const bf
 }
 
 // x[m][n] += sum_ks part[ks][m][n];  xb = bf16(x) in GEMM-operand layout
-__global__ void resid_reduce_kernel(const float *__restrict__ part, int ksplit, int M, int N, float *__restrict__ x,
-                                    bf16_t *__restrict__ xb) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)M * N) return;
-    float v = x[idx];
-    for (int k = 0; k < ksplit; ++k) v += part[(size_t)k * M * N + idx];
-    x[idx] = v;
-    xb[Layout<bf16_t>::a_index((int)(idx / N), (int)(idx % N), N)] = float_to_bf16(v);
+// grid (ceil(N / 256), M).  ssq_part (may be NULL): [M][gridDim.x] sums of squares of the bf16 values this block wrote.
+__global__ __launch_bounds__(256) void resid_reduce_kernel(const float *__restrict__ part, int ksplit, int M, int N, float *__restrict__ x,
+                                                           bf16_t *__restrict__ xb, float *__restrict__ ssq_part) {
+    const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+    float sq = 0.0f;
+    if (n < N) {
+        const size_t idx = (size_t)m * N + n;
+        float v = x[idx];
+        for (int k = 0; k < ksplit; ++k) v += part[(size_t)k * M * N + idx];
+        x[idx] = v;
+        const bf16_t b = float_to_bf16(v);
+        xb[Layout<bf16_t>::a_index(m, n, N)] = b;
+        sq = bf16_to_float(b) * bf16_to_float(b);
+    }
+    if (ssq_part) {
+        __shared__ float scratch[17];
+        const float t = block_sum_f32(sq, scratch);
+        if (threadIdx.x == 0) ssq_part[(size_t)m * gridDim.x + blockIdx.x] = t;
+    }
 }
 
 template <int EPI, int NW>

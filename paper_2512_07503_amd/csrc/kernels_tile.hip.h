@@ -15,47 +15,47 @@
 // loaded cacheable: the row tiles of a column tile run side by side and the second one finds them in L2.
 //
 // Epilogues and operand layouts are those of the small-row kernel (skinny_epilogue): column blocks (0, 1) and
-// (2, 3) of a tile are rotary / gate-up pairs.  RMSNorm row sums of squares come from the activation fragments as
-// they are consumed.
+// (2, 3) of a tile are rotary / gate-up pairs.  RMSNorm row sums of squares come from the kernel that wrote the
+// rows (partial sums per row, added in a fixed order by the epilogue) when it provides them, else from the
+// activation fragments as they are consumed - which costs a third of the loop's issue slots.
 #pragma once
 #include "kernels_skinny.hip.h"
 
 constexpr int TILE_M = 256, TILE_N = 128;
 constexpr int TILE_KS = 1;    // k-steps (of 16) per pipeline stage, i.e. per workgroup barrier
-constexpr int TILE_RING = 4;  // stages of global loads in flight per wavefront (KS x RING = 4 k-steps measured best)
+#ifndef SJD_TILE_RING
+#define SJD_TILE_RING 4
+#endif
+constexpr int TILE_RING = SJD_TILE_RING;  // stages of global loads in flight per wavefront
 
-template <int EPI, int KS = TILE_KS, int D = TILE_RING, int MINW = 2>
-__global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int n_blocks, int row_tiles32, int col_tiles, int row_tiles) {
+template <int EPI, bool SSQ_LOOP = true, int RT = 2, int KS = TILE_KS, int D = TILE_RING>
+__global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyArgs a, int n_blocks, int row_tiles32, int col_tiles, int row_tiles) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
+    constexpr bool kSsqLoop = kNorm && SSQ_LOOP;  // else the rows' sums of squares come from the kernel that wrote the rows
     constexpr int U = D % 2 == 0 ? D : 2 * D;  // unroll: ring slot and LDS buffer of an iteration are compile-time
+    constexpr int TM = 128 * RT;              // rows of the workgroup's tile: wavefront w owns rows [32 RT w, 32 RT (w + 1))
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // blockIdx.x -> (column tile ct, row tile rt).  Workgroups go to the 8 XCDs round-robin by linear id: keep the
-    // row tiles of one column tile on one XCD (they share the weights in its L2) when the count allows it.
-    int ct, rt;
-    {
-        const int id = blockIdx.x, span = 8 * row_tiles;
-        if (col_tiles % 8 == 0) {
-            ct = (id / span) * 8 + (id & 7);
-            rt = (id % span) >> 3;
-        } else {
-            ct = id / row_tiles;
-            rt = id % row_tiles;
-        }
-    }
+    // blockIdx.x -> (column tile ct, row tile rt).  Workgroups go to the 8 XCDs round-robin by linear id, and every
+    // XCD has its own L2: all row tiles of a column tile run on XCD ct % 8, so that its weights are fetched from HBM
+    // by one L2 only.  id = 8 j + x enumerates XCD x's list of (column tile x + 8 (j / row_tiles), row tile
+    // j % row_tiles); the grid is padded to 8 ceil(col_tiles / 8) column tiles and the padding exits here.
+    const int ct = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 3) / row_tiles), rt = (blockIdx.x >> 3) % row_tiles;
+    if (ct >= col_tiles) return;
     const int KB = a.KB, ks = blockIdx.y;
     const int kb_lo = ks * a.kb_per_split;
     const int kb_hi = kb_lo + a.kb_per_split < KB ? kb_lo + a.kb_per_split : KB;
     const int n_k = kb_hi - kb_lo;             // k-steps of this workgroup
     const int n_it = (n_k + KS - 1) / KS;      // pipeline stages
 
-    // this wavefront's operands: activation row tiles (of 32) 8 rt + 2 wave + {0, 1}, straight into registers;
+    // this wavefront's operands: activation row tiles (of 32) RT (4 rt + wave) + {0 .. RT - 1}, straight into registers;
     // weight block 4 ct + wave, its share of the stage in LDS.  Indices past the end are clamped (their
     // products land in rows / columns the epilogue never stores).
-    const int ra0 = min(rt * 8 + 2 * wave, row_tiles32 - 1), ra1 = min(rt * 8 + 2 * wave + 1, row_tiles32 - 1);
+    const u32x4 *Aj[RT];
+#pragma unroll
+    for (int j = 0; j < RT; ++j)
+        Aj[j] = reinterpret_cast<const u32x4 *>(a.A) + (size_t)min((rt * 4 + wave) * RT + j, row_tiles32 - 1) * KB * 64 + lane;
     const int rb = min(ct * 4 + wave, n_blocks - 1);
-    const u32x4 *A0 = reinterpret_cast<const u32x4 *>(a.A) + (size_t)ra0 * KB * 64 + lane;
-    const u32x4 *A1 = reinterpret_cast<const u32x4 *>(a.A) + (size_t)ra1 * KB * 64 + lane;
     const u32x4 *B0 = reinterpret_cast<const u32x4 *>(a.W) + (size_t)rb * KB * 64 + lane;
 
     // k-loop: stage[buffer][k-step of the stage][weight block][lane]; epilogue: 8 KiB per wavefront to index its
@@ -63,28 +63,28 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
     __shared__ u32x4 smem[2048];
     static_assert(2 * KS * 4 * 64 <= 2048, "stage buffers exceed the LDS array");
     u32x4 (*stage)[KS][4][64] = reinterpret_cast<u32x4 (*)[KS][4][64]>(smem);
-    __shared__ float ssq_lds[4][2][32];
+    __shared__ float ssq_lds[4][RT][32];
 
-    f32x16 acc[2][4];
+    f32x16 acc[RT][4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < RT; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
-    float ssq[2] = {0.0f, 0.0f};
+    float ssq[RT];
+#pragma unroll
+    for (int j = 0; j < RT; ++j) ssq[j] = 0.0f;
 
     if (n_it > 0) {
-        u32x4 ra[D][KS][2], rbw[D][KS];
+        u32x4 ra[D][KS][RT], rbw[D][KS];
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
         // k-steps past the end re-read the last fragments (cache hits); their activations are zeroed when consumed
 #define TILE_KB(step, q) ((size_t)(kb_lo + min((step) * KS + (q), n_k - 1)) * 64)
 #define TILE_LOAD_A(slot, step)                                                             \
     do {                                                                                    \
-        _Pragma("unroll") for (int q_ = 0; q_ < KS; ++q_) {                                 \
-            ra[slot][q_][0] = A0[TILE_KB(step, q_)];                                        \
-            ra[slot][q_][1] = A1[TILE_KB(step, q_)];                                        \
-        }                                                                                   \
+        _Pragma("unroll") for (int q_ = 0; q_ < KS; ++q_)                                   \
+            _Pragma("unroll") for (int j_ = 0; j_ < RT; ++j_) ra[slot][q_][j_] = Aj[j_][TILE_KB(step, q_)]; \
     } while (0)
 #define TILE_LOAD_B(slot, step)                                                             \
     do {                                                                                    \
@@ -105,56 +105,71 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
         TILE_LOAD_B(0, D);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        for (int it0 = 0; it0 < n_it; it0 += U) {
+        // one pipeline stage: su = position in the unrolled group (ring slot and LDS buffer are compile-time)
+        auto stage_step = [&](int su, int it) {
+            const int slot = su % D, nslot = (su + 1) % D, cur = su & 1;
+            bf16x8 bfr[KS][4];
 #pragma unroll
-            for (int su = 0; su < U; ++su) {
-                const int it = it0 + su;
-                const int slot = su % D, nslot = (su + 1) % D, cur = su & 1;
-                bf16x8 bfr[KS][4];
+            for (int q = 0; q < KS; ++q)
 #pragma unroll
-                for (int q = 0; q < KS; ++q)
+                for (int i = 0; i < 4; ++i) bfr[q][i] = __builtin_bit_cast(bf16x8, stage[cur][q][i][lane]);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) bfr[q][i] = __builtin_bit_cast(bf16x8, stage[cur][q][i][lane]);
+            for (int q = 0; q < KS; ++q) {
+                const bool valid = KS == 1 || it * KS + q < n_k;   // KS = 1: every stage that runs is a real k-step
 #pragma unroll
-                for (int q = 0; q < KS; ++q) {
-                    const bool valid = it * KS + q < n_k;
+                for (int j = 0; j < RT; ++j) {
+                    const u32x4 araw = valid ? ra[slot][q][j] : zero4;
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, araw);
+                    if (kSsqLoop) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const u32x4 araw = valid ? ra[slot][q][j] : zero4;
-                        const bf16x8 av = __builtin_bit_cast(bf16x8, araw);
-                        if (kNorm) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const uint32_t pr = araw[e];
-                                const float lo = __builtin_bit_cast(float, pr << 16), hi = __builtin_bit_cast(float, pr & 0xFFFF0000u);
-                                ssq[j] = fmaf(lo, lo, ssq[j]);
-                                ssq[j] = fmaf(hi, hi, ssq[j]);
-                            }
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t pr = araw[e];
+                            const float lo = __builtin_bit_cast(float, pr << 16), hi = __builtin_bit_cast(float, pr & 0xFFFF0000u);
+                            ssq[j] = fmaf(lo, lo, ssq[j]);
+                            ssq[j] = fmaf(hi, hi, ssq[j]);
                         }
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bfr[q][i], acc[j][i], 0, 0, 0);
                     }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bfr[q][i], acc[j][i], 0, 0, 0);
                 }
-                TILE_LOAD_A(slot, it + D);
-                // the next stage's weights into the other buffer (nobody reads it before the barrier below)
-                TILE_STORE_B(cur ^ 1, nslot, it + 1);
-                TILE_LOAD_B(nslot, it + 1 + D);
-                __builtin_amdgcn_sched_barrier(0);
-                __syncthreads();
             }
+            TILE_LOAD_A(slot, it + D);
+            // the next stage's weights into the other buffer (nobody reads it before the barrier below)
+            TILE_STORE_B(cur ^ 1, nslot, it + 1);
+            TILE_LOAD_B(nslot, it + 1 + D);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        };
+        // Whole groups of U stages run without a test (the matrix cores are the bound here: every vector
+        // instruction in this loop takes issue slots from the MFMAs); the last n_it % U stages behind uniform branches.
+        int it0 = 0;
+        for (; it0 + U <= n_it; it0 += U) {
+#pragma unroll
+            for (int su = 0; su < U; ++su) stage_step(su, it0 + su);
         }
+#pragma unroll
+        for (int su = 0; su < U; ++su)
+            if (it0 + su < n_it) stage_step(su, it0 + su);
 #undef TILE_KB
 #undef TILE_LOAD_A
 #undef TILE_LOAD_B
 #undef TILE_STORE_B
     }
 
-    if (kNorm) {
+    if (kSsqLoop) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < RT; ++j) {
             const float t = ssq[j] + __shfl_xor(ssq[j], 32, 64);
             if (lane < 32) ssq_lds[wave][j][lane] = t;
         }
+        __syncthreads();
+    } else if (kNorm) {
+        // row tid of the tile: its partial sums of squares in their fixed order
+        const int m = rt * TM + tid;
+        float t = 0.0f;
+        if (tid < TM && m < a.M)
+            for (int c = 0; c < a.row_ssq_n; ++c) t += a.row_ssq_part[(size_t)m * a.row_ssq_n + c];
+        if (tid < TM) ssq_lds[tid / (32 * RT)][(tid >> 5) % RT][tid & 31] = t;
         __syncthreads();
     }
     // The epilogue body is long; unrolled 64 times it would exceed what the compiler unrolls, and a rolled loop
@@ -163,14 +178,14 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
     const int col = lane & 31;
     float *park = reinterpret_cast<float *>(smem) + wave * 2048 + lane;
     // QKV: the row-dependent part of the destination (integer divisions, page lookup) once per row, not per element
-    __shared__ QkvRow qrow[EPI == EPI_QKV ? TILE_M : 1];
+    __shared__ QkvRow qrow[EPI == EPI_QKV ? TM : 1];
     if (EPI == EPI_QKV) {
-        const int m = rt * TILE_M + tid;
-        if (m < a.M) qrow[EPI == EPI_QKV ? tid : 0] = qkv_row(a, m);
+        const int m = rt * TM + tid;
+        if (tid < TM && m < a.M) qrow[EPI == EPI_QKV ? tid : 0] = qkv_row(a, m);
         __syncthreads();
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < RT; ++j)
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int g = ct * 2 + p;
@@ -182,13 +197,13 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
 #pragma unroll 1
             for (int v = 0; v < 16; ++v) {
                 const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int m = rt * TILE_M + (wave * 2 + j) * 32 + row;
+                const int m = rt * TM + (wave * RT + j) * 32 + row;
                 if (m >= a.M) continue;
                 float inv = 1.0f;
                 if (kNorm) inv = 1.0f / sqrtf(ssq_lds[wave][j][row] / (float)(KB * 16) + a.eps);
                 const float vals[2] = {park[v * 64], park[(16 + v) * 64]};
                 if constexpr (EPI == EPI_QKV) {
-                    const QkvRow &r = qrow[(wave * 2 + j) * 32 + row];
+                    const QkvRow &r = qrow[(wave * RT + j) * 32 + row];
                     float c, sn;
                     qkv_rotation(a, m, g, col, c, sn);
                     qkv_store(a, r, g, col, vals[0] * inv, vals[1] * inv, c, sn);
@@ -207,13 +222,35 @@ __global__ __launch_bounds__(256, MINW) void gemm_tile_kernel(SkinnyArgs a, int 
         }
 }
 
+// Rows per workgroup tile for n_blocks column blocks over M rows.  256 rows (two 32-row tiles per wavefront) need
+// the fewest operand bytes per MFMA: 0.75 KiB against 1.25 KiB for 128 rows, whose weight fragments alone would
+// take the whole LDS bandwidth at full MFMA rate.  128 rows are chosen where they spread the work better: when
+// 256-row tiles would not even fill the CUs, or when the most loaded CU (a launch takes as long as that one)
+// gets less work - ceil(workgroups / 256) tiles of 256 rows against as many half-size ones.
+inline int tile_rows_for(int M, int n_blocks, int ksplit) {
+    const int col_tiles = (n_blocks + 3) / 4;
+    const long wg2 = (long)col_tiles * ((M + 255) / 256) * ksplit, wg1 = (long)col_tiles * ((M + 127) / 128) * ksplit;
+    if (wg2 < 256) return 128;
+    const long cost2 = 2 * ((wg2 + 255) / 256), cost1 = (wg1 + 255) / 256;
+    return cost1 < cost2 ? 128 : 256;
+}
+
 // n_blocks = packed 32-column blocks of W.  The K range of a workgroup is a.kb_per_split k-blocks (grid.y = a.ksplit).
 template <int EPI>
-inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks) {
+inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks, int tile_rows = 0) {
     if (a.M <= 0 || n_blocks <= 0 || a.KB <= 0 || a.ksplit < 1 || (size_t)a.kb_per_split * a.ksplit < (size_t)a.KB) return hipErrorInvalidValue;
     if (EPI != EPI_PARTIAL && a.ksplit != 1) return hipErrorInvalidValue;
-    const int row_tiles32 = (a.M + 31) / 32, row_tiles = (a.M + TILE_M - 1) / TILE_M, col_tiles = (n_blocks + 3) / 4;
-    const dim3 grid(col_tiles * row_tiles, a.ksplit);
-    gemm_tile_kernel<EPI><<<grid, 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, row_tiles);
+    if (tile_rows == 0) tile_rows = tile_rows_for(a.M, n_blocks, a.ksplit);
+    const int row_tiles32 = (a.M + 31) / 32, row_tiles = (a.M + tile_rows - 1) / tile_rows, col_tiles = (n_blocks + 3) / 4;
+    const dim3 grid(8 * ((col_tiles + 7) / 8) * row_tiles, a.ksplit);
+    constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
+    const bool ssq_loop = !(kNorm && a.row_ssq_part);
+    if (tile_rows == 128) {
+        if (ssq_loop) gemm_tile_kernel<EPI, true, 1><<<grid, 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, row_tiles);
+        else gemm_tile_kernel<EPI, false, 1><<<grid, 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, row_tiles);
+    } else {
+        if (ssq_loop) gemm_tile_kernel<EPI, true, 2><<<grid, 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, row_tiles);
+        else gemm_tile_kernel<EPI, false, 2><<<grid, 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, row_tiles);
+    }
     return hipGetLastError();
 }

@@ -73,6 +73,7 @@ struct sjd_ctx {
     int attn_chunk = 0, attn_nchunks = 0;
     bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
     float *part_o = nullptr, *part_ml = nullptr;
+    float *row_ssq = nullptr;              // [M][ceil(d / 256)] partial sums of squares of the residual stream's rows
     QkvRow *row_meta = nullptr;            // per-row tables of the fused path, rewritten by every forward
     float2 *row_rot = nullptr;
     bool l2_warm = true;                   // projection launches touch the next projection's weights
@@ -309,6 +310,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
                    rt.row_pos = c->rm.row_pos; rt.rope_cos = c->rope_cos; rt.rope_sin = c->rope_sin;
                    rt.page_table = c->page_table; rt.pages_per_seg = c->pps; rt.page_tokens = c->pt;
                    rt.L = c->L; rt.H = H; rt.hd = hd; rt.meta = c->row_meta; rt.rot = c->row_rot;
+                   rt.ssq_part = c->row_ssq; rt.ssq_n = ceil_div(d, 256);
                    embed_dual_kernel<<<M, 256, 0, st>>>((const bf16_t *)c->tok_emb, c->rm.row_tok, c->x, (bf16_t *)c->xn, d, rt);
                }));
     SkinnyArgs a;
@@ -370,9 +372,16 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.pf_sink = c->pf_sink;
     };
     const Proj none = {nullptr, 0, 0, 0, false};
+    // Many-row kernels take the RMSNorm row sums of squares from the kernel that wrote the residual stream (embedding
+    // gather or split-K reduction) instead of accumulating them in their k-loops
+    const int tile_rows = (md.kernel_flags & SJD_TILES_256_ROWS) ? 256 : 0;  // 0: chosen per launch
+    bool ssq_ready = true;   // the embedding kernel wrote them
+    float *const ssq_out = tile ? c->row_ssq : nullptr;
+    auto use_ssq = [&]() { a.row_ssq_part = tile && ssq_ready ? c->row_ssq : nullptr; a.row_ssq_n = ceil_div(d, 256); };
     auto resid = [&](int cls, const void *A, const void *W, int K, const Proj &nx, const KvPool *kv_next) -> int {
         a.A = (const bf16_t *)A; a.W = (const bf16_t *)W; a.KB = K / 16; a.N = d;
         a.pf_wgs = 0;
+        a.row_ssq_part = nullptr;
         if (tile) {
             const int n_blocks = ceil_div(d, 64) * 2, wgs = ceil_div(n_blocks, 4) * ceil_div(M, TILE_M);
             int ks = std::min(8, std::max(1, 256 / wgs));
@@ -380,15 +389,17 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             a.kb_per_split = ceil_div(a.KB, ks);
             a.ksplit = ceil_div(a.KB, a.kb_per_split);
             if (a.ksplit == 1) {
-                SJD_LAUNCH(c, cls, launch_tile<EPI_RESID>(st, a, n_blocks));
+                SJD_LAUNCH(c, cls, launch_tile<EPI_RESID>(st, a, n_blocks, tile_rows));
+                ssq_ready = false;
                 return SJD_OK;
             }
             if ((size_t)a.ksplit * M * d > c->skinny_part_elems) return no_room();
-            SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks));
+            SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks, tile_rows));
             const int ksplit = a.ksplit;
             SJD_LAUNCH(c, KC_ADDNORM, after([&] {
-                           resid_reduce_kernel<<<ceil_div(M * d, 256), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn);
+                           resid_reduce_kernel<<<dim3(ceil_div(d, 256), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
                        }));
+            ssq_ready = true;
             return SJD_OK;
         }
         const int groups = ceil_div(ceil_div(d, 32), nbw_d);
@@ -412,7 +423,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         SJD_LAUNCH(c, cls, launch_skinny<EPI_PARTIAL>(st, a, MT, groups, nbw_d, nw_for(groups * a.ksplit)));
         const int ksplit = a.ksplit;
         SJD_LAUNCH(c, KC_ADDNORM, after([&] {
-                       resid_reduce_kernel<<<ceil_div(M * d, 256), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn);
+                       resid_reduce_kernel<<<dim3(ceil_div(d, 256), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
                    }));
         return SJD_OK;
     };
@@ -428,7 +439,8 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wqkv; a.KB = d / 16;
         if (tile) {
             whole_k();
-            SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2));
+            use_ssq();
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2, tile_rows));
         } else {
             whole_k();
             warm(groups_qkv, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
@@ -441,7 +453,8 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)lw.wgu; a.KB = d / 16;
         if (tile) {
             whole_k();
-            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2));
+            use_ssq();
+            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2, tile_rows));
         } else {
             whole_k();
             warm(F / 32, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
@@ -460,7 +473,8 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
         if (tile) {
             whole_k();
-            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2));
+            use_ssq();
+            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2, tile_rows));
         } else {
             whole_k();
             SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
@@ -612,6 +626,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         c->skinny_part_elems = std::max((size_t)widest * 8 * (2 * 2 * 1024 + 64), (size_t)8 * M * d);
         if ((rc = dev_alloc(c, &c->skinny_part, c->skinny_part_elems * sizeof(float)))) return rc;
         if ((rc = dev_alloc(c, &c->pf_sink, 256))) return rc;
+        if ((rc = dev_alloc(c, &c->row_ssq, (size_t)M * ceil_div(d, 256) * sizeof(float)))) return rc;
         if ((rc = dev_alloc(c, &c->row_meta, (size_t)M * sizeof(QkvRow)))) return rc;
         if ((rc = dev_alloc(c, &c->row_rot, (size_t)M * (hd / 2) * sizeof(float2)))) return rc;
         c->l2_warm = !(md.kernel_flags & SJD_NO_L2_WARM);

@@ -40,6 +40,8 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
                                         ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
                                         ("small_tile", 16), ("small_tile", 0), ("small_fused64", 8),
+                                        # flags 16 + 64: 256-row workgroup tiles (the default picks 128 rows here)
+                                        ("small_tile", 80),
                                         # flag 32: no extra workgroups that warm the next launch's operands into L2
                                         ("small_fused64", 32),
                                         # flag 2: kernels launched one by one instead of the replayed HIP graph
@@ -129,7 +131,9 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
                                                               # 7B-class contexts use (these short twins would not)
                                                               ("cfg1", 2, 120, 6, 1, 8), ("cfg3", 2, 64, 3, 1, 8),
                                                               # without the L2 warm-up workgroups
-                                                              ("cfg1", 2, 120, 6, 1, 32)])
+                                                              ("cfg1", 2, 120, 6, 1, 32),
+                                                              # 256-row workgroup tiles
+                                                              ("cfg4", 2, 64, 2, 5, 64)])
 def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
