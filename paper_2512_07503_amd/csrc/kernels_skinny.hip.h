@@ -215,19 +215,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         return;
     }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
-    // blockIdx.x enumerates (column group g, row group mg).  With several row groups the order is chosen so that
-    // the row groups of one column group are dispatched close together AND to the same XCD (workgroups go to
-    // XCDs round-robin by linear id): id = (g / 8) * 8 * m_groups + mg * 8 + g % 8, so they share the weights in L2.
+    // blockIdx.x enumerates (column group g, row group mg).  With several row groups all row groups of a column
+    // group run on XCD g % 8 (workgroups go to XCDs round-robin by linear id, and every XCD has its own L2), so that
+    // one L2 fetches the group's weights from HBM: id = 8 j + x is entry j of XCD x's list of
+    // (g = x + 8 (j / m_groups), mg = j % m_groups); the grid is padded to 8 ceil(groups / 8) groups.
     int g = blockIdx.x, mg = 0;
     if (a.m_groups > 1) {
-        const int id = blockIdx.x, span = 8 * a.m_groups;
-        if (a.groups % 8 == 0) {
-            g = (id / span) * 8 + (id & 7);
-            mg = (id % span) >> 3;
-        } else {
-            g = id / a.m_groups;
-            mg = id % a.m_groups;
-        }
+        g = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 3) / a.m_groups);
+        mg = (blockIdx.x >> 3) % a.m_groups;
+        if (g >= a.groups) return;
     }
     const int KB = a.KB, m_base = mg * MT * 32;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
@@ -531,7 +527,7 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     SkinnyArgs a = a_in;
     a.groups = groups;
     if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = a.kv_wgs = 0;
-    const dim3 grid(groups * (a.m_groups > 1 ? a.m_groups : 1) + a.pf_wgs + a.kv_wgs, a.ksplit);
+    const dim3 grid(a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : groups + a.pf_wgs + a.kv_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
