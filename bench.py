@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg1")
     ap.add_argument("--trace-steps", type=int, default=20)
+    ap.add_argument("--trace-skip", type=int, default=0,
+                    help="untimed steps between the prefill and the traced steps: per-kernel durations deep in the image "
+                         "(long cache) instead of at its start")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps in the CPU baseline (0 = sized to ~20 s)")
     ap.add_argument("--kernel-flags", type=int, default=0)
@@ -170,10 +173,16 @@ def main():
     forwards_per_image = float(np.mean(images_steps)) if images_steps else None
 
     # ---- per-kernel durations with HIP events on the library's stream, right after the timed region
+    tokens_done = [0] * S
+    for _ in range(args.trace_skip):
+        dec.step_raw(res)
+        for s in range(S):
+            tokens_done[s] += res[s].n_finalized
+        if all(res[s].done for s in range(S)):
+            break
     dec.trace(True)
     dec.trace_reset()
     traced, mean_ctx_sum = 0, 0
-    tokens_done = [0] * S
     for _ in range(args.trace_steps):
         mean_ctx_sum += P - 1 + tokens_done[0]
         dec.step_raw(res)

@@ -358,27 +358,53 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
 }
 
 // Merges the chunks of every (row, head): out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
-__global__ void attention_combine_kernel(AttnArgs a) {
-    const int m = blockIdx.x, h = blockIdx.y;
-    const int seg = m / a.L, i_win = m % a.L, hd = a.hd;
+// Workgroup = one wavefront on 8 window rows of one (segment, head, query tile): lane = (row, eighth of the head
+// dimensions).  The chunk loops carry no dependence from one load to the next (the maximum first, then the
+// weights), so the partial results of all chunks are in flight together.
+template <int HD>
+__global__ __launch_bounds__(64) void attention_combine_kernel(AttnArgs a) {
+    constexpr int DPT = HD / 8;  // head dimensions per lane
+    const int rq = blockIdx.x & 3, pair = blockIdx.x >> 2;
+    const int qt = pair % a.n_qt, sh = pair / a.n_qt, h = sh % a.H, seg = sh / a.H;
+    const int iq = rq * 8 + (threadIdx.x >> 3), dg = threadIdx.x & 7;
+    const int i_win = 32 * qt + iq;
+    if (i_win >= a.L) return;
+    const int m = seg * a.L + i_win;
     const bool active = a.row_tok[m] >= 0;
-    const int n_tot = a.seg_kv[seg] + a.seg_n[seg];
-    const int qt = i_win >> 5, iq = i_win & 31;
-    const int n_vis = min(n_tot, a.seg_kv[seg] + 32 * (qt + 1));  // the chunks this row's query tile went through
+    const int kv = a.seg_kv[seg];
+    const int n_vis = min(kv + a.seg_n[seg], kv + 32 * (qt + 1));  // the chunks this row's query tile went through
     const int nc = active ? (n_vis + a.chunk - 1) / a.chunk : 0;
-    const size_t slot0 = (((size_t)seg * a.H + h) * a.n_qt + qt) * a.n_chunks;
+    const size_t slot0 = (size_t)pair * a.n_chunks;
+    const float *ml = a.part_ml + slot0 * 64 + iq;
     float mx = -INFINITY;
-    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, a.part_ml[(slot0 + c) * 64 + iq]);
+#pragma unroll 4
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, ml[(size_t)c * 64]);
     float denom = 0.0f;
-    for (int c = 0; c < nc; ++c) denom += exp2f(a.part_ml[(slot0 + c) * 64 + iq] - mx) * a.part_ml[(slot0 + c) * 64 + 32 + iq];
-    const float inv = nc > 0 ? 1.0f / denom : 0.0f;
-    for (int j = threadIdx.x; j < hd; j += blockDim.x) {
-        float acc = 0.0f;
-        for (int c = 0; c < nc; ++c)
-            acc += exp2f(a.part_ml[(slot0 + c) * 64 + iq] - mx) * a.part_o[(slot0 + c) * 32 * hd + (size_t)iq * hd + j];
-        acc *= inv;
-        if (a.out_act) a.out_act[Layout<bf16_t>::a_index(m, h * hd + j, a.H * hd)] = float_to_bf16(acc);
-        if (a.out_plain) a.out_plain[((size_t)m * a.H + h) * hd + j] = acc;
+    float acc[DPT];
+#pragma unroll
+    for (int d = 0; d < DPT; ++d) acc[d] = 0.0f;
+    const float *po = a.part_o + slot0 * 32 * HD + (size_t)iq * HD + dg * DPT;
+#pragma unroll 4
+    for (int c = 0; c < nc; ++c) {
+        const float w = exp2f(ml[(size_t)c * 64] - mx);
+        denom = fmaf(w, ml[(size_t)c * 64 + 32], denom);
+        const float4 *p4 = reinterpret_cast<const float4 *>(po + (size_t)c * 32 * HD);
+#pragma unroll
+        for (int v = 0; v < DPT / 4; ++v) {
+            const float4 x = p4[v];
+            acc[4 * v] = fmaf(w, x.x, acc[4 * v]);
+            acc[4 * v + 1] = fmaf(w, x.y, acc[4 * v + 1]);
+            acc[4 * v + 2] = fmaf(w, x.z, acc[4 * v + 2]);
+            acc[4 * v + 3] = fmaf(w, x.w, acc[4 * v + 3]);
+        }
+    }
+    const float inv = nc > 0 && denom > 0.0f ? 1.0f / denom : 0.0f;
+#pragma unroll
+    for (int d = 0; d < DPT; ++d) {
+        const int j = dg * DPT + d;
+        const float v = acc[d] * inv;
+        if (a.out_act) a.out_act[Layout<bf16_t>::a_index(m, h * HD + j, a.H * HD)] = float_to_bf16(v);
+        if (a.out_plain) a.out_plain[((size_t)m * a.H + h) * HD + j] = v;
     }
 }
 
@@ -403,6 +429,8 @@ inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n
     else attention_mfma_kernel<128><<<grid, G * 64, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    attention_combine_kernel<<<dim3(n_segments * a.L, a.H), a.hd <= 64 ? 64 : 128, 0, st>>>(a);
+    const int combine_wgs = n_segments * a.H * a.n_qt * 4;
+    if (a.hd == 64) attention_combine_kernel<64><<<combine_wgs, 64, 0, st>>>(a);
+    else attention_combine_kernel<128><<<combine_wgs, 64, 0, st>>>(a);
     return hipGetLastError();
 }
