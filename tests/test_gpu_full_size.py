@@ -1,12 +1,18 @@
 """The 7B-class benchmark shapes at full depth, width, vocabulary and batch, in the launch configuration bench.py
 times (fused / tile kernels, replayed graph).
 
-The double-precision oracle needs hours for one forward of these models, so what is checked here are properties
-that hold at any size:
-  * the first decoding step's logits agree, within the bf16 tolerance, with those of the plain reference kernels
-    (`KERNELS_REFERENCE`: no MFMA, separate normalisation / rotary / SwiGLU kernels, no fused epilogues - code that
-    shares nothing with the fused path and that test_gpu_e2e.py holds to the oracle on depth-reduced twins of the
-    same shapes);
+The double-precision oracle needs hours for one forward of these models, so the reference here is the library's own
+fp32 mode (plain fp32 kernels, no bf16 anywhere; test_gpu_e2e.py holds it to the oracle at 1e-4 on small shapes and
+at the cfg0 shape) run on the same bf16-valued weights, and what is checked are properties that hold at any size:
+  * the first decoding step's logits of the bf16 fused path stay within what bf16 activations cost at this depth.
+    A rounding point costs 2^-9 relative, a layer has about six (projection inputs, queries / keys / values,
+    probabilities, attention output, MLP hidden), and the errors add in quadrature: sqrt(6 x 32) x 2^-9 = 2.7e-2
+    before the model amplifies them.  Measured at 32 layers: 4.5e-2 - 5.0e-2 of a row's largest |logit| (1.0e-2 at
+    2 layers, 1.9e-2 at 8: the square-root growth), so the 3e-2 that the depth-reduced twins and the 36-layer cfg1
+    shape are held to is out of reach of the format here; the bound is 6e-2;
+  * the fused path is no further from fp32 than an independent bf16 implementation of the same forward, the plain
+    reference kernels (`KERNELS_REFERENCE`: no MFMA, separate normalisation / rotary / SwiGLU kernels), which
+    measure 5.5e-2 - 6.1e-2: the distance is the format's, not the kernels';
   * a step is reproducible bit for bit (restore the state saved before it and run it again), verdicts included.
 Decisions at these vocabulary sizes are compared with the oracle in test_gpu_decide.py.
 """
@@ -20,7 +26,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("name,S", [("cfg2", 1), ("cfg3", 1), ("cfg4", 8)])
-def test_full_size_step_agrees_with_the_plain_kernels_and_is_reproducible(name, S):
+def test_full_size_step_against_the_fp32_path(name, S):
     import torch
     import paper_2512_07503_amd as sjd
     from workload.generate import make_weights_torch
@@ -30,14 +36,13 @@ def test_full_size_step_agrees_with_the_plain_kernels_and_is_reproducible(name, 
     weights = make_weights_torch(arch, cfg["seed"], cfg["head_alpha"], "cuda", torch.bfloat16)
     cond, uncond = workload.make_prompts(arch, cfg["seed"], S, P)
 
-    def decoder(flags):
-        d = sjd.Decoder(arch, weights, cfg["dtype"], L, P + N, max_seqs=S, cfg_scale=cfg["cfg_scale"],
-                        temperature=cfg["temperature"], top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"],
-                        kernel_flags=flags)
+    def decoder(flags, dtype, w):
+        d = sjd.Decoder(arch, w, dtype, L, P + N, max_seqs=S, cfg_scale=cfg["cfg_scale"], temperature=cfg["temperature"],
+                        top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"], kernel_flags=flags)
         assert d.prefill(cond, uncond, [N] * S) == 0
         return d
 
-    g = decoder(0)
+    g = decoder(0, "bf16", weights)
     les = [g.window(s)[2] for s in range(S)]
     snap = g.snapshot()
     res = g.step()
@@ -47,10 +52,17 @@ def test_full_size_step_agrees_with_the_plain_kernels_and_is_reproducible(name, 
     g.restore(snap)
     assert g.step() == res
     assert np.array_equal(g.logits(), got)
-    # an independent implementation of the forward
-    r = decoder(sjd.KERNELS_REFERENCE)
-    del weights
+    del g
+    r = decoder(sjd.KERNELS_REFERENCE, "bf16", weights)
     r.step()
-    err = logits_error(got, r.logits(), les)
-    print(name, "fused vs plain kernels, worst |d| and worst |d| / max|logit| of a row:", err)
-    assert err[1] <= 3e-2, err
+    plain = r.logits()
+    del r
+    w32 = {k: ([t.float() for t in v] if isinstance(v, list) else v.float()) for k, v in weights.items()}
+    del weights
+    f = decoder(0, "f32", w32)
+    f.step()
+    want = f.logits()
+    err_fused, err_plain = logits_error(got, want, les), logits_error(plain, want, les)
+    print(name, "worst |d| / max|logit| of a row against fp32: fused", err_fused[1], "plain bf16 kernels", err_plain[1])
+    assert err_fused[1] <= 6e-2, err_fused
+    assert err_fused[1] <= 1.1 * err_plain[1], (err_fused, err_plain)
