@@ -632,8 +632,11 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         c->l2_warm = !(md.kernel_flags & SJD_NO_L2_WARM);
     }
     if (c->attn_mfma) {
-        // chunk length: about 1500 wavefronts at full context, at least 128 tokens, a multiple of 64
-        long want = (long)md.max_ctx * S * 2 * H * ceil_div(L, 32) / 1500;
+        // chunk length: about 640 wavefronts at full context (measured: every chunk costs a partial result of
+        // 32 x hd floats per head, written and read back, which at 128-token chunks is as many bytes as the keys and
+        // values themselves; fewer, longer chunks win until the workgroups no longer fill the chip), at least 128
+        // tokens, a multiple of 64
+        long want = (long)md.max_ctx * S * 2 * H * ceil_div(L, 32) / 640;
         int chunk = (int)((want + 63) / 64) * 64;
         if (chunk < 128) chunk = 128;
         c->attn_chunk = chunk;
