@@ -221,8 +221,9 @@ __global__ void sample_rows_kernel(SampleRowsArgs a) {
 // Register-resident form for V <= 1024 * VPT: the guided logits of a row are read from HBM once and stay in
 // registers (thread t holds elements t, t + 1024, ...).  The K-th largest key is found one bit at a time, most
 // significant first: count the candidates whose next bit is 1; if at least `want` of them exist the K-th
-// largest has that bit set, otherwise it does not and `want` drops by that count.  32 counting rounds of a
-// wavefront ballots and one LDS exchange each, no atomics, exact.
+// largest has that bit set, otherwise it does not and `want` drops by that count.  32 counting rounds of
+// wavefront ballots and one LDS exchange each, exact; after the first 10 bits the rounds run over the compacted
+// list of keys that still compete (see below).
 // adds one wave-uniform count per wavefront over the block; scratch alternates between rounds
 SJD_D uint32_t block_sum_wave_counts(uint32_t wave_count, uint32_t *scratch /* [16] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
     const uint32_t par = a.step ? (*a.step & 1u) : 0u;
     float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
     const int V = a.V, tid = threadIdx.x;
-    __shared__ uint32_t cnt[2][16];
+    __shared__ uint32_t cnt[2][16], cnt2[16];
     __shared__ uint32_t scratch32[17];
     __shared__ uint64_t scratch64[17];
 
@@ -260,7 +261,8 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
     uint32_t thresh = 0;
     if (a.top_k < V) {
         uint32_t prefix = 0, want = (uint32_t)a.top_k;
-        for (int bit = 31; bit >= 0; --bit) {
+        // one counting round over the keys in registers
+        auto round_all = [&](int bit) {
             const uint32_t hi_mask = bit == 31 ? 0u : ~((2u << bit) - 1u);  // bits above `bit`
             const uint32_t probe = prefix | (1u << bit);
             uint32_t c = 0;  // wave-uniform: ballots, not shuffles
@@ -268,6 +270,46 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
             for (int i = 0; i < VPT; ++i) c += (uint32_t)__popcll(__ballot((key[i] & (hi_mask | (1u << bit))) == probe));
             c = block_sum_wave_counts(c, cnt[bit & 1]);
             if (c >= want) prefix = probe; else want -= c;
+        };
+        // The top kSplitBits bits (sign, exponent, first mantissa bit) over all keys.  What still competes for the
+        // K-th place afterwards are the keys that share those bits with it: usually a few percent of the row.  If
+        // they fit the LDS list they are compacted (any order: the rounds only count) and the remaining rounds run
+        // over at most kCandPerThread keys per thread instead of VPT; otherwise the rounds go on over all keys.
+        constexpr int kSplitBits = 10, kCandPerThread = 4, kCandMax = 1024 * kCandPerThread;
+        for (int bit = 31; bit > 31 - kSplitBits; --bit) round_all(bit);
+        constexpr uint32_t top_mask = ~((1u << (32 - kSplitBits)) - 1u);
+        __shared__ uint32_t cand[kCandMax];
+        __shared__ uint32_t n_cand_lds;
+        uint32_t n_cand = 0;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) n_cand += (uint32_t)__popcll(__ballot((key[i] & top_mask) == prefix));
+        n_cand = block_sum_wave_counts(n_cand, cnt2);
+        if (n_cand <= (uint32_t)kCandMax) {
+            if (tid == 0) n_cand_lds = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < VPT; ++i)
+                if ((key[i] & top_mask) == prefix) cand[atomicAdd(&n_cand_lds, 1u)] = key[i];
+            __syncthreads();
+            uint32_t ck[kCandPerThread];
+            bool cv[kCandPerThread];
+#pragma unroll
+            for (int j = 0; j < kCandPerThread; ++j) {
+                cv[j] = (uint32_t)(tid + 1024 * j) < n_cand;
+                ck[j] = cv[j] ? cand[tid + 1024 * j] : 0u;
+            }
+            for (int bit = 31 - kSplitBits; bit >= 0; --bit) {
+                const uint32_t hi_mask = ~((2u << bit) - 1u);
+                const uint32_t probe = prefix | (1u << bit);
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = 0; j < kCandPerThread; ++j)
+                    c += (uint32_t)__popcll(__ballot(cv[j] && (ck[j] & (hi_mask | (1u << bit))) == probe));
+                c = block_sum_wave_counts(c, cnt[bit & 1]);
+                if (c >= want) prefix = probe; else want -= c;
+            }
+        } else {
+            for (int bit = 31 - kSplitBits; bit >= 0; --bit) round_all(bit);
         }
         thresh = prefix;
     }
