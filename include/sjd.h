@@ -63,9 +63,11 @@ enum {
     SJD_NO_L2_WARM = 32,       /* bf16, <= 64 rows: projection launches carry no extra
                                 * workgroups that touch the next launch's weights and
                                 * key/value pages into L2 (same results either way)    */
-    SJD_TILES_256_ROWS = 64    /* bf16, >= 256 rows: every tile kernel launch uses 256-row
+    SJD_TILES_256_ROWS = 64,   /* bf16, >= 256 rows: every tile kernel launch uses 256-row
                                 * workgroup tiles (default: 128-row tiles where they
                                 * balance the CUs better)                              */
+    SJD_NO_ROW_SPLIT = 128     /* bf16, 17..32 rows: projections of at most 64 column groups
+                                * with one workgroup per group (default: two, 16 rows each) */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

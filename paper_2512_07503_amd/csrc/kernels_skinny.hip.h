@@ -39,6 +39,7 @@ struct SkinnyArgs {
     int M, KB;
     int groups;        // column groups (set by the launcher)
     int m_groups;      // row groups of MT * 32 rows, each run by its own workgroups over the same weights (M > 64)
+    int row_split;     // 2: (one 32-row tile, whole K) two workgroups per column group, 16 rows each; else 1
     float eps;
     // RESID
     float *x;          // [M][N] fp32 residual stream, updated in place
@@ -209,9 +210,11 @@ template <int MT, int NBW, int NW, int DEPTH, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
-    if ((int)blockIdx.x >= a.groups && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
-        if ((int)blockIdx.x < a.groups + a.pf_wgs) l2_warm_next(a, blockIdx.x, a.groups, tid, NW * 64);
-        else l2_warm_kv(a, blockIdx.x, a.groups + a.pf_wgs, tid, NW * 64);
+    // computing workgroups come first: one per column group, or (row_split 2) two, listed per XCD like row groups
+    const int n_compute = a.row_split == 2 ? 16 * ((a.groups + 7) / 8) : a.groups;
+    if ((int)blockIdx.x >= n_compute && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
+        if ((int)blockIdx.x < n_compute + a.pf_wgs) l2_warm_next(a, blockIdx.x, n_compute, tid, NW * 64);
+        else l2_warm_kv(a, blockIdx.x, n_compute + a.pf_wgs, tid, NW * 64);
         return;
     }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
@@ -225,6 +228,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         mg = (blockIdx.x >> 3) % a.m_groups;
         if (g >= a.groups) return;
     }
+    // row_split 2: this workgroup computes rows [16 half, 16 half + 16) of the 32-row tile only.  The loop is bound
+    // by what the CU's L1 delivers, and half the rows are half the activation lines (lane l of a fragment holds row
+    // l % 32, so the other half's lanes simply do not load); the MFMAs run on zeros for them, which costs nothing here.
+    int half = 0;
+    if (a.row_split == 2) {
+        g = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 4));
+        half = (blockIdx.x >> 3) & 1;
+        if (g >= a.groups) return;
+    }
+    const bool a_lane = a.row_split != 2 || ((lane >> 4) & 1) == half;
     const int KB = a.KB, m_base = mg * MT * 32;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
     const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + (size_t)mg * MT * KB * 64 + lane;
@@ -258,13 +271,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
                     for (int i = 0; i < NBW; ++i) {
                         const int n = (g * NBW + i) * 32 + (lane & 31);
-                        xpre[j][i][hh] = m < a.M && n < a.N ? a.x[(size_t)m * a.N + n] : 0.0f;
+                        xpre[j][i][hh] = m < a.M && n < a.N && (a.row_split != 2 || ((m >> 4) & 1) == half) ? a.x[(size_t)m * a.N + n] : 0.0f;
                     }
                 } else {
                     qrow[j][hh].pos = -1;
                     rot_c[j][hh] = 1.0f;
                     rot_s[j][hh] = 0.0f;
-                    if (m < a.M) {
+                    if (m < a.M && (a.row_split != 2 || ((m >> 4) & 1) == half)) {
                         qrow[j][hh] = qkv_row(a, m);
                         qkv_rotation(a, m, g, lane & 31, rot_c[j][hh], rot_s[j][hh]);
                     }
@@ -293,7 +306,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
             for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
-            for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+            for (int j = 0; j < MT; ++j) aq[s][j] = a_lane ? Ap[((size_t)j * KB + kb) * 64] : u32x4{0u, 0u, 0u, 0u};
         }
         __builtin_amdgcn_sched_barrier(0);
         auto consume = [&](int s) {
@@ -320,7 +333,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
             for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
-            for (int j = 0; j < MT; ++j) aq[s][j] = Ap[((size_t)j * KB + kb) * 64];
+            for (int j = 0; j < MT; ++j) aq[s][j] = a_lane ? Ap[((size_t)j * KB + kb) * 64] : u32x4{0u, 0u, 0u, 0u};
         };
         // Steady state: groups of DEPTH iterations whose refills are all fragments that will be used.  The body is
         // branch-free so that the compiler counts outstanding loads exactly (a slot is consumed while the
@@ -391,7 +404,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             const int v = wave + NW * hh;
             const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             const int m = m_base + j * 32 + row;
-            if (m >= a.M) continue;
+            if (m >= a.M || (a.row_split == 2 && (row >> 4) != half)) continue;
             float inv = 1.0f;
             if (kNorm) {
                 float t = 0.0f;
@@ -527,7 +540,9 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     SkinnyArgs a = a_in;
     a.groups = groups;
     if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = a.kv_wgs = 0;
-    const dim3 grid(a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : groups + a.pf_wgs + a.kv_wgs, a.ksplit);
+    if (a.row_split == 2 && (MT != 1 || a.m_groups > 1 || a.ksplit != 1 || EPI == EPI_PARTIAL)) return hipErrorInvalidValue;
+    const int n_compute = a.row_split == 2 ? 16 * ((groups + 7) / 8) : groups;
+    const dim3 grid(a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : n_compute + a.pf_wgs + a.kv_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);

@@ -371,6 +371,10 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.kv_pool = pool;
         a.pf_sink = c->pf_sink;
     };
+    // few column groups and one 32-row tile: two workgroups per group, 16 rows each (half the activation lines per
+    // workgroup; the loop is bound by what a CU's L1 delivers).  Measured on the 36 x 1280 shape: output, down and QKV
+    // projections (40-60 groups) gain, gate/up (108 groups: too few CUs left for the warm-up workgroups) loses.
+    auto row_split_for = [&](int groups) { return MT == 1 && M > 16 && groups <= 64 && !(md.kernel_flags & SJD_NO_ROW_SPLIT) ? 2 : 1; };
     const Proj none = {nullptr, 0, 0, 0, false};
     // Many-row kernels take the RMSNorm row sums of squares from the kernel that wrote the residual stream (embedding
     // gather or split-K reduction) instead of accumulating them in their k-loops
@@ -411,10 +415,13 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         }
         if (ks == 1) {
             whole_k();
-            warm(groups, nx);
-            if (kv_next) warm_kv(groups, *kv_next);
+            a.row_split = row_split_for(groups);
+            const int n_compute = a.row_split == 2 ? 16 * ceil_div(groups, 8) : groups;
+            warm(n_compute, nx);
+            if (kv_next) warm_kv(n_compute, *kv_next);
             SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
             a.pf_wgs = a.kv_wgs = 0;
+            a.row_split = 1;
             return SJD_OK;
         }
         a.kb_per_split = ceil_div(a.KB, ks);
@@ -443,10 +450,13 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2, tile_rows));
         } else {
             whole_k();
-            warm(groups_qkv, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
-            if (l == 0) warm_kv(groups_qkv, pool);  // later layers: requested by the down projection before them
+            a.row_split = row_split_for(groups_qkv);
+            const int n_compute = a.row_split == 2 ? 16 * ceil_div(groups_qkv, 8) : groups_qkv;
+            warm(n_compute, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
+            if (l == 0) warm_kv(n_compute, pool);  // later layers: requested by the down projection before them
             SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, groups_qkv, 2, nw_for(groups_qkv)));
             a.pf_wgs = a.kv_wgs = 0;
+            a.row_split = 1;
         }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
         { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd, Proj{lw.wgu, F / 32, 2, d / 16, true}, nullptr); if (rc) return rc; }
@@ -457,9 +467,12 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2, tile_rows));
         } else {
             whole_k();
-            warm(F / 32, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
+            a.row_split = row_split_for(F / 32);
+            const int n_compute = a.row_split == 2 ? 16 * ceil_div(F / 32, 8) : F / 32;
+            warm(n_compute, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
             SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
             a.pf_wgs = 0;
+            a.row_split = 1;
         }
         const Proj after_down = l + 1 < md.n_layers ? Proj{c->layers[l + 1].wqkv, groups_qkv, 2, d / 16, true}
                                 : with_head         ? Proj{c->lm_head, ceil_div(ceil_div(c->Vs, 32), 2), 2, d / 16, true}

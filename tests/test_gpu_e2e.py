@@ -44,6 +44,8 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
                                         ("small_tile", 80),
                                         # flag 32: no extra workgroups that warm the next launch's operands into L2
                                         ("small_fused64", 32),
+                                        # flag 128: one workgroup per column group instead of two with 16 rows each
+                                        ("small_fused64", 128), ("small_fused128", 128),
                                         # flag 2: kernels launched one by one instead of the replayed HIP graph
                                         ("small_f32", 2), ("small_fused64", 2), ("small_sub", 2)])
 def test_small_models_step_by_step(oracle, name, flags):
@@ -131,7 +133,7 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
                                                               # 7B-class contexts use (these short twins would not)
                                                               ("cfg1", 2, 120, 6, 1, 8), ("cfg3", 2, 64, 3, 1, 8),
                                                               # without the L2 warm-up workgroups
-                                                              ("cfg1", 2, 120, 6, 1, 32),
+                                                              ("cfg1", 2, 120, 6, 1, 32), ("cfg1", 2, 120, 6, 1, 128),
                                                               # 256-row workgroup tiles
                                                               ("cfg4", 2, 64, 2, 5, 64)])
 def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags):
