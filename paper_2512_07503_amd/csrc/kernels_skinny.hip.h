@@ -206,12 +206,12 @@ SJD_D void l2_warm_kv(const SkinnyArgs &a, int id, int first_id, int tid, int th
     if (sink == 0x9e3779b9u) *a.pf_sink = sink;
 }
 
-template <int MT, int NBW, int NW, int DEPTH, int EPI>
+template <int MT, int NBW, int NW, int DEPTH, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
     const int tid = threadIdx.x, lane = tid & 63;
     // computing workgroups come first: one per column group, or (row_split 2) two, listed per XCD like row groups
-    const int n_compute = a.row_split == 2 ? 16 * ((a.groups + 7) / 8) : a.groups;
+    const int n_compute = SPLIT ? 16 * ((a.groups + 7) / 8) : a.groups;
     if ((int)blockIdx.x >= n_compute && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
         if ((int)blockIdx.x < n_compute + a.pf_wgs) l2_warm_next(a, blockIdx.x, n_compute, tid, NW * 64);
         else l2_warm_kv(a, blockIdx.x, n_compute + a.pf_wgs, tid, NW * 64);
@@ -232,12 +232,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     // by what the CU's L1 delivers, and half the rows are half the activation lines (lane l of a fragment holds row
     // l % 32, so the other half's lanes simply do not load); the MFMAs run on zeros for them, which costs nothing here.
     int half = 0;
-    if (a.row_split == 2) {
+    if (SPLIT) {
         g = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 4));
         half = (blockIdx.x >> 3) & 1;
         if (g >= a.groups) return;
     }
-    const bool a_lane = a.row_split != 2 || ((lane >> 4) & 1) == half;
+    const bool a_lane = !SPLIT || ((lane >> 4) & 1) == half;  // SPLIT false: a constant, the loads below stay unconditional
     const int KB = a.KB, m_base = mg * MT * 32;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
     const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + (size_t)mg * MT * KB * 64 + lane;
@@ -271,13 +271,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
                     for (int i = 0; i < NBW; ++i) {
                         const int n = (g * NBW + i) * 32 + (lane & 31);
-                        xpre[j][i][hh] = m < a.M && n < a.N && (a.row_split != 2 || ((m >> 4) & 1) == half) ? a.x[(size_t)m * a.N + n] : 0.0f;
+                        xpre[j][i][hh] = m < a.M && n < a.N && (!SPLIT || ((m >> 4) & 1) == half) ? a.x[(size_t)m * a.N + n] : 0.0f;
                     }
                 } else {
                     qrow[j][hh].pos = -1;
                     rot_c[j][hh] = 1.0f;
                     rot_s[j][hh] = 0.0f;
-                    if (m < a.M && (a.row_split != 2 || ((m >> 4) & 1) == half)) {
+                    if (m < a.M && (!SPLIT || ((m >> 4) & 1) == half)) {
                         qrow[j][hh] = qkv_row(a, m);
                         qkv_rotation(a, m, g, lane & 31, rot_c[j][hh], rot_s[j][hh]);
                     }
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             const int v = wave + NW * hh;
             const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             const int m = m_base + j * 32 + row;
-            if (m >= a.M || (a.row_split == 2 && (row >> 4) != half)) continue;
+            if (m >= a.M || (SPLIT && (row >> 4) != half)) continue;
             float inv = 1.0f;
             if (kNorm) {
                 float t = 0.0f;
@@ -545,12 +545,14 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     const dim3 grid(a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : n_compute + a.pf_wgs + a.kv_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
-        if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
+        if (MT == 1 && a.row_split == 2) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI, true><<<grid, NW * 64, 0, st>>>(a);
+        else if (MT == 1) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
         else gemm_skinny_kernel<2, 2, NW, DEPTH, EPI><<<grid, NW * 64, 0, st>>>(a);
     } else {
         if (kPair) return hipErrorInvalidValue;
         constexpr int E1 = kPair ? EPI_RESID : EPI;
-        if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
+        if (MT == 1 && a.row_split == 2) gemm_skinny_kernel<1, 1, NW, DEPTH, E1, true><<<grid, NW * 64, 0, st>>>(a);
+        else if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
         else gemm_skinny_kernel<2, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
     }
     return hipGetLastError();
