@@ -66,8 +66,15 @@ enum {
     SJD_TILES_256_ROWS = 64,   /* bf16, >= 256 rows: every tile kernel launch uses 256-row
                                 * workgroup tiles (default: 128-row tiles where they
                                 * balance the CUs better)                              */
-    SJD_NO_ROW_SPLIT = 128     /* bf16, 17..32 rows: projections of at most 64 column groups
+    SJD_NO_ROW_SPLIT = 128,    /* bf16, 17..32 rows: projections of at most 64 column groups
                                 * with one workgroup per group (default: two, 16 rows each) */
+    SJD_NO_MIXED_WIDTH = 256,  /* bf16, <= 64 rows: gate/up and head projections of more than
+                                * 256 column groups with one workgroup per group (default:
+                                * one workgroup per CU, some of them two groups wide)   */
+    SJD_NO_K_ROTATION = 512    /* bf16, row-group projection kernels: every workgroup walks K
+                                * from 0 (default: each starts at its own offset and wraps,
+                                * so that they do not all ask for the same activation lines
+                                * at the same time; sums differ in the last bits only)  */
 };
 
 /* Architecture and capacities; plain data, copied by sjd_create.

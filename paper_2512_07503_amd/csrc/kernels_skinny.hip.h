@@ -19,8 +19,14 @@
 // the MFMA consumes, and the row scale 1/rms is applied to the accumulators (it commutes with the
 // contraction).
 #pragma once
+#include <algorithm>
+
 #include "common.hip.h"
 #include "kernels_forward.hip.h"
+
+#ifndef SJD_SKINNY_DEPTH
+#define SJD_SKINNY_DEPTH 8   // slots of the operand ring of a wavefront
+#endif
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PARTIAL = 4 };
 
@@ -40,6 +46,8 @@ struct SkinnyArgs {
     int groups;        // column groups (set by the launcher)
     int m_groups;      // row groups of MT * 32 rows, each run by its own workgroups over the same weights (M > 64)
     int row_split;     // 2: (one 32-row tile, whole K) two workgroups per column group, 16 rows each; else 1
+    int k_rot;         // 1: workgroup id starts its k-loop (id / 8) iterations in (see skinny_body), 0: all start at k = 0
+    int n_heavy;       // mixed-width launch (set by its launcher): workgroups [0, n_heavy) take two column groups each
     float eps;
     // RESID
     float *x;          // [M][N] fp32 residual stream, updated in place
@@ -126,22 +134,22 @@ SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float
     }
 }
 
-// One output element pair of the projection epilogues: row m, column `col` of the NBW column blocks of group g
-// (val[i] = block g * NBW + i), inv = 1 / rms of row m (1 where the epilogue does not normalise).
+// One output element pair of the projection epilogues: row m, column `col` of NBW consecutive column blocks
+// (val[i] = block blk0 + i), inv = 1 / rms of row m (1 where the epilogue does not normalise).
 // xin: the residual-stream values x[m][n_i] (RESID only; the caller loads them, early if it can).
 template <int EPI, int NBW>
-SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, const float (&val)[NBW], float inv,
+SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int blk0, int col, const float (&val)[NBW], float inv,
                            const float (&xin)[NBW]) {
     if constexpr (EPI == EPI_PARTIAL) {
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
-            const int n = (g * NBW + i) * 32 + col;
+            const int n = (blk0 + i) * 32 + col;
             if (n < a.N) a.part[((size_t)ks * a.M + m) * a.N + n] = val[i];
         }
     } else if constexpr (EPI == EPI_RESID) {
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
-            const int n = (g * NBW + i) * 32 + col;
+            const int n = (blk0 + i) * 32 + col;
             if (n < a.N) {
                 const float nv = xin[i] + val[i];
                 a.x[(size_t)m * a.N + n] = nv;
@@ -151,14 +159,18 @@ SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int g, int col, c
     } else if constexpr (EPI == EPI_HEAD) {
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
-            const int n = (g * NBW + i) * 32 + col;
+            const int n = (blk0 + i) * 32 + col;
             if (n < a.N) a.logits[(size_t)m * a.N + n] = val[i] * inv;
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
-        // tile 0 = gate columns [32 g, 32 g + 32), tile 1 = the matching up columns
-        const float gt = val[0] * inv, up = val[1] * inv;
-        const int n = g * 32 + col;
-        if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
+        // blocks come in pairs: gate columns [32 p, 32 p + 32) in block 2 p, the matching up columns in block 2 p + 1
+        static_assert(NBW % 2 == 0, "gate and up blocks come in pairs");
+#pragma unroll
+        for (int i = 0; i < NBW; i += 2) {
+            const float gt = val[i] * inv, up = val[i + 1] * inv;
+            const int n = ((blk0 + i) >> 1) * 32 + col;
+            if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
+        }
     } else {
         static_assert(EPI != EPI_QKV, "the QKV epilogue is qkv_row + qkv_rotation + qkv_store, called by the kernels");
     }
@@ -206,10 +218,12 @@ SJD_D void l2_warm_kv(const SkinnyArgs &a, int id, int first_id, int tid, int th
     if (sink == 0x9e3779b9u) *a.pf_sink = sink;
 }
 
+template <int MT, int NBW, int NW, int DEPTH, int EPI, bool SPLIT>
+SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0);
+
 template <int MT, int NBW, int NW, int DEPTH, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
-    constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x;
     // computing workgroups come first: one per column group, or (row_split 2) two, listed per XCD like row groups
     const int n_compute = SPLIT ? 16 * ((a.groups + 7) / 8) : a.groups;
     if ((int)blockIdx.x >= n_compute && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
@@ -217,7 +231,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         else l2_warm_kv(a, blockIdx.x, n_compute + a.pf_wgs, tid, NW * 64);
         return;
     }
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
     // blockIdx.x enumerates (column group g, row group mg).  With several row groups all row groups of a column
     // group run on XCD g % 8 (workgroups go to XCDs round-robin by linear id, and every XCD has its own L2), so that
     // one L2 fetches the group's weights from HBM: id = 8 j + x is entry j of XCD x's list of
@@ -237,15 +250,47 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         half = (blockIdx.x >> 3) & 1;
         if (g >= a.groups) return;
     }
+    skinny_body<MT, NBW, NW, DEPTH, EPI, SPLIT>(a, g, mg, half, g * NBW);
+}
+
+// Workgroups of two widths in one launch, for more than 256 column groups of two blocks (gate/up and vocabulary
+// head of the wide models).  A CU keeps a bounded number of bytes in flight, and every workgroup pulls all 64 x K
+// activations beside its weights: with one group per workgroup some CUs get two workgroups (2 x (weights +
+// activations)) while the others idle half the time.  Here the first n_heavy workgroups take two consecutive groups
+// (4 blocks: one pass over the activations for both) and the others one, n_heavy + (groups - 2 n_heavy) workgroups in
+// all: 256 for up to 512 groups.  The register count admits one workgroup per CU, so each CU gets one.
+template <int MT, int NW, int DEPTH, int EPI>
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_mixed_kernel(SkinnyArgs a) {
+    static_assert(EPI == EPI_SWIGLU || EPI == EPI_HEAD, "epilogues that take any even number of blocks");
+    const int w = blockIdx.x;
+    // (the wide body's ring has 3/4 of the slots: 6 fragments per slot instead of 4, more bytes in flight all the same)
+    if (w < a.n_heavy) skinny_body<MT, 4, NW, DEPTH * 3 / 4, EPI, false>(a, 2 * w, 0, 0, 4 * w);
+    else skinny_body<MT, 2, NW, DEPTH, EPI, false>(a, a.n_heavy + w, 0, 0, 2 * (a.n_heavy + w));
+}
+
+// The workgroup's work: column blocks [blk0, blk0 + NBW) (column group g of the QKV epilogue), row group mg.
+template <int MT, int NBW, int NW, int DEPTH, int EPI, bool SPLIT>
+SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
+    constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the k-loop control flow scalar
     const bool a_lane = !SPLIT || ((lane >> 4) & 1) == half;  // SPLIT false: a constant, the loads below stay unconditional
     const int KB = a.KB, m_base = mg * MT * 32;
-    const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)g * NBW * KB * 64 + lane;
+    const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.W) + (size_t)blk0 * KB * 64 + lane;
     const u32x4 *Ap = reinterpret_cast<const u32x4 *>(a.A) + (size_t)mg * MT * KB * 64 + lane;
     // this workgroup's k-blocks: [kb_lo, kb_hi); wavefront w takes kb_lo + w, kb_lo + w + NW, ...
     const int ks = blockIdx.y;
     const int kb_lo = ks * a.kb_per_split;
     const int kb_hi = kb_lo + a.kb_per_split < KB ? kb_lo + a.kb_per_split : KB;
     const int n_it = kb_lo + wave < kb_hi ? (kb_hi - kb_lo - wave + NW - 1) / NW : 0;
+    // All workgroups of a launch read the same activation fragments; started together at k = 0 they would ask the same
+    // L2 channel for the same lines at the same time all the way.  Workgroup id therefore walks its k-blocks in the
+    // rotated order rot, rot + 1, ..., n_it - 1, 0, ..., rot - 1 (ids 8 apart share an XCD's L2: rot = id / 8).
+    const int rot = n_it > 0 ? (int)(((blockIdx.x >> 3) * (unsigned)a.k_rot) % (unsigned)n_it) : 0;
+    auto kb_of = [&](int it) {
+        const int r = it + rot;
+        return (size_t)(kb_lo + wave + (r >= n_it ? r - n_it : r) * NW);
+    };
 #ifdef SJD_PHASE_TIMING
 #define SJD_STAMP(i) do { if (a.phase && tid == 0) a.phase[g * 8 + (i)] = wall_clock64(); } while (0)
 #else
@@ -270,7 +315,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 if (EPI == EPI_RESID) {
 #pragma unroll
                     for (int i = 0; i < NBW; ++i) {
-                        const int n = (g * NBW + i) * 32 + (lane & 31);
+                        const int n = (blk0 + i) * 32 + (lane & 31);
                         xpre[j][i][hh] = m < a.M && n < a.N && (!SPLIT || ((m >> 4) & 1) == half) ? a.x[(size_t)m * a.N + n] : 0.0f;
                     }
                 } else {
@@ -302,7 +347,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
         u32x4 bq[DEPTH][NBW], aq[DEPTH][MT];
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-            const size_t kb = (size_t)(kb_lo + wave + (s < n_it ? s : n_it - 1) * NW);
+            const size_t kb = kb_of(s < n_it ? s : n_it - 1);
 #pragma unroll
             for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
@@ -329,7 +374,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
             }
         };
         auto refill = [&](int s, int it) {
-            const size_t kb = (size_t)(kb_lo + wave + it * NW);
+            const size_t kb = kb_of(it);
 #pragma unroll
             for (int i = 0; i < NBW; ++i) bq[s][i] = __builtin_nontemporal_load(Wp + ((size_t)i * KB + kb) * 64);
 #pragma unroll
@@ -419,7 +464,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
                 xin[i] = EPI == EPI_RESID ? xpre[j][i][hh] : 0.0f;
             }
             if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[j][hh], g, col, vals[0] * inv, vals[NBW - 1] * inv, rot_c[j][hh], rot_s[j][hh]);
-            else skinny_epilogue<EPI, NBW>(a, ks, m, g, col, vals, inv, xin);
+            else skinny_epilogue<EPI, NBW>(a, ks, m, blk0, col, vals, inv, xin);
         }
     SJD_STAMP(3);
 }
@@ -533,9 +578,6 @@ __global__ __launch_bounds__(256) void resid_reduce_kernel(const float *__restri
 
 template <int EPI, int NW>
 inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int MT, int groups, int nbw) {
-#ifndef SJD_SKINNY_DEPTH
-#define SJD_SKINNY_DEPTH 8
-#endif
     constexpr int DEPTH = SJD_SKINNY_DEPTH;
     SkinnyArgs a = a_in;
     a.groups = groups;
@@ -555,6 +597,25 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
         else if (MT == 1) gemm_skinny_kernel<1, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
         else gemm_skinny_kernel<2, 1, NW, DEPTH, E1><<<grid, NW * 64, 0, st>>>(a);
     }
+    return hipGetLastError();
+}
+
+// More than 256 column groups of two blocks, one row group, whole K, 4 wavefronts: 256 workgroups (groups <= 512),
+// the first groups - 256 of them two groups wide; beyond 512 groups every workgroup is two groups wide.
+inline bool skinny_mixed_applies(const SkinnyArgs &a, int groups, int nbw, int nw) {
+    return groups > 256 && nbw == 2 && nw == 4 && a.m_groups <= 1 && a.ksplit == 1 && a.row_split != 2;
+}
+template <int EPI>
+inline hipError_t launch_skinny_mixed(hipStream_t st, const SkinnyArgs &a_in, int MT, int groups) {
+    constexpr int DEPTH = SJD_SKINNY_DEPTH;
+    SkinnyArgs a = a_in;
+    if (!skinny_mixed_applies(a, groups, 2, 4) || MT < 1 || MT > 2) return hipErrorInvalidValue;
+    a.groups = groups;
+    a.pf_wgs = a.kv_wgs = 0;
+    a.n_heavy = std::min(groups / 2, groups - 256);
+    const int light = groups - 2 * a.n_heavy;
+    if (MT == 1) gemm_skinny_mixed_kernel<1, 4, DEPTH, EPI><<<a.n_heavy + light, 256, 0, st>>>(a);
+    else gemm_skinny_mixed_kernel<2, 4, DEPTH, EPI><<<a.n_heavy + light, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 

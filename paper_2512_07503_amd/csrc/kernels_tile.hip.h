@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
                             if (n < a.N) xin[i] = a.x[(size_t)m * a.N + n];
                         }
                     }
-                    skinny_epilogue<EPI, 2>(a, ks, m, g, col, vals, inv, xin);
+                    skinny_epilogue<EPI, 2>(a, ks, m, g * 2, col, vals, inv, xin);
                 }
             }
         }

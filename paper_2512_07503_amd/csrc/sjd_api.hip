@@ -319,6 +319,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     a.m_groups = m_groups;
     a.eps = md.rms_eps;
     a.row_meta = c->row_meta;
+    a.k_rot = (md.kernel_flags & SJD_NO_K_ROTATION) ? 0 : 1;
     a.row_rot = c->row_rot;
     a.q_out = (bf16_t *)c->q;
     a.L = c->L; a.H = H; a.Hkv = Hkv; a.hd = hd; a.F = F;
@@ -376,6 +377,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     // projections (40-60 groups) gain, gate/up (108 groups: too few CUs left for the warm-up workgroups) loses.
     auto row_split_for = [&](int groups) { return MT == 1 && M > 16 && groups <= 64 && !(md.kernel_flags & SJD_NO_ROW_SPLIT) ? 2 : 1; };
     const Proj none = {nullptr, 0, 0, 0, false};
+    const bool mixed_ok = !(md.kernel_flags & SJD_NO_MIXED_WIDTH);
     // Many-row kernels take the RMSNorm row sums of squares from the kernel that wrote the residual stream (embedding
     // gather or split-K reduction) instead of accumulating them in their k-loops
     const int tile_rows = (md.kernel_flags & SJD_TILES_256_ROWS) ? 256 : 0;  // 0: chosen per launch
@@ -470,7 +472,8 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             a.row_split = row_split_for(F / 32);
             const int n_compute = a.row_split == 2 ? 16 * ceil_div(F / 32, 8) : F / 32;
             warm(n_compute, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
-            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+            if (mixed_ok && skinny_mixed_applies(a, F / 32, 2, nw_for(F / 32))) SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny_mixed<EPI_SWIGLU>(st, a, MT, F / 32));
+            else SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
             a.pf_wgs = 0;
             a.row_split = 1;
         }
@@ -490,7 +493,9 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2, tile_rows));
         } else {
             whole_k();
-            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, ceil_div(ceil_div(c->Vs, 32), 2), 2, nw_for(ceil_div(c->Vs, 64))));
+            const int groups_v = ceil_div(ceil_div(c->Vs, 32), 2);
+            if (mixed_ok && skinny_mixed_applies(a, groups_v, 2, nw_for(groups_v))) SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny_mixed<EPI_HEAD>(st, a, MT, groups_v));
+            else SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, groups_v, 2, nw_for(groups_v)));
         }
     }
     return SJD_OK;

@@ -46,6 +46,8 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
                                         ("small_fused64", 32),
                                         # flag 128: one workgroup per column group instead of two with 16 rows each
                                         ("small_fused64", 128), ("small_fused128", 128),
+                                        # flag 512: every workgroup walks K from 0 instead of from its own offset
+                                        ("small_fused64", 512), ("small_fused128", 512),
                                         # flag 2: kernels launched one by one instead of the replayed HIP graph
                                         ("small_f32", 2), ("small_fused64", 2), ("small_sub", 2)])
 def test_small_models_step_by_step(oracle, name, flags):
@@ -126,23 +128,28 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
     print("cfg0 steps", steps, "worst logits error abs/rel:", worst)
 
 
-@pytest.mark.parametrize("name,layers,prompt,steps,S,flags", [("cfg1", 36, 24, 3, 1, 0), ("cfg1", 2, 120, 40, 1, 0),
-                                                              ("cfg2", 2, 64, 3, 1, 0), ("cfg3", 2, 64, 3, 1, 0),
-                                                              ("cfg4", 2, 64, 3, 3, 0), ("cfg4", 2, 64, 2, 5, 0),
+@pytest.mark.parametrize("name,layers,prompt,steps,S,flags,window", [("cfg1", 36, 24, 3, 1, 0, None), ("cfg1", 2, 120, 40, 1, 0, None),
+                                                              # gate/up and head of the 7B shapes: workgroups of two widths
+                                                              # (344 groups: 88 wide + 168; 448: 192 + 64; heads: all wide)
+                                                              ("cfg2", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 3, 1, 0, None),
+                                                              # ... with a single 32-row tile, and one group per workgroup
+                                                              ("cfg2", 2, 64, 3, 1, 0, 12), ("cfg3", 2, 64, 2, 1, 256, None),
+                                                              ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None),
                                                               # the chunk + merge attention kernels the full-length
                                                               # 7B-class contexts use (these short twins would not)
-                                                              ("cfg1", 2, 120, 6, 1, 8), ("cfg3", 2, 64, 3, 1, 8),
+                                                              ("cfg1", 2, 120, 6, 1, 8, None), ("cfg3", 2, 64, 3, 1, 8, None),
                                                               # without the L2 warm-up workgroups
-                                                              ("cfg1", 2, 120, 6, 1, 32), ("cfg1", 2, 120, 6, 1, 128),
+                                                              ("cfg1", 2, 120, 6, 1, 32, None), ("cfg1", 2, 120, 6, 1, 128, None),
+                                                              ("cfg1", 2, 120, 6, 1, 512, None), ("cfg2", 2, 64, 2, 1, 512, None),
                                                               # 256-row workgroup tiles
-                                                              ("cfg4", 2, 64, 2, 5, 64)])
-def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags):
+                                                              ("cfg4", 2, 64, 2, 5, 64, None)])
+def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags, window):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
     cfg = workload.get_config(name)
     arch = dict(cfg["arch"], n_layers=layers)
     w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16")
-    o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S,
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S, window=window,
                                           n_image=min(cfg["n_image"], 200), kernel_flags=flags)
     worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)
     print(name, layers, "worst logits error abs/rel:", worst)
