@@ -249,11 +249,25 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
 
     uint32_t key[VPT];  // order key of the guided logit; 0 (below every real key) past the end of the row
     uint32_t kmax = 0;
+    // The loads are unconditional (index clamped to the row) and issued in batches: a load under `if (v < V)` is
+    // waited for inside its branch, and a thread would pay one memory round trip per element.
+    constexpr int kBatch = VPT < 16 ? VPT : 16;
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-        const int v = tid + i * 1024;
-        key[i] = v < V ? order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t)) : 0u;
-        kmax = key[i] > kmax ? key[i] : kmax;
+    for (int i0 = 0; i0 < VPT; i0 += kBatch) {
+        float c[kBatch], u[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
+            c[j] = lc[vv];
+            u[j] = lu[vv];
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int i = i0 + j, v = tid + i * 1024;
+            const uint32_t kk = order_key(guided(c[j], u[j], a.cfg_scale, a.inv_t));
+            key[i] = v < V ? kk : 0u;
+            kmax = key[i] > kmax ? key[i] : kmax;
+        }
     }
     kmax = block_max_u32(kmax, scratch32);
     const float m = key_to_float(kmax);

@@ -58,18 +58,26 @@ def test_decisions_bit_exact_cfg0_shape(oracle):
     assert st["acc"] > 0 and st["rej"] > 0
 
 
-def test_decisions_bit_exact_large_vocab(oracle):
-    """V_s = 65536, K = 2000, L = 32 (the 7B-shaped configurations), two sequences, a few steps."""
-    cfg = workload.get_config("cfg2")
+@pytest.mark.parametrize("name,top_k,flat", [("cfg2", None, False),
+                                             # V_s = 16384: K = 1000 (the kept entries fit the kernel's list), K = 6000
+                                             # (they do not: plain pass over the row), K = V_s (no top-K at all)
+                                             ("cfg1", None, False), ("cfg1", 6000, False), ("cfg1", 16384, False),
+                                             # a row of few distinct values: thousands of ties with the K-th largest
+                                             ("cfg1", None, True)])
+def test_decisions_bit_exact_large_vocab(oracle, name, top_k, flat):
+    """V_s = 65536, K = 2000, L = 32 (the 7B-shaped configurations) and V_s = 16384, two sequences, a few steps."""
+    cfg = workload.get_config(name)
     cfg["arch"] = dict(cfg["arch"], d_model=64, n_heads=2, n_kv_heads=2, d_ff=64)   # only V_s matters here
     import helpers
-    o, g, *_ = helpers.make_pair(oracle, cfg, window=32, n_image=80, prompt_len=3, n_seqs=2, n_layers=1)
+    o, g, *_ = helpers.make_pair(oracle, cfg, window=32, n_image=80, prompt_len=3, n_seqs=2, n_layers=1, top_k=top_k)
     rng = np.random.default_rng(5)
     Vs = o.Vs
     base = (rng.standard_normal((2, 2, 120, Vs)) * 2.5).astype(np.float32)
+    if flat:
+        base = np.round(base)   # integers -9 .. 9
     pos = [0, 0]
     for step in range(6):
-        lg = np.stack([base[s, :, pos[s]: pos[s] + 32] + (rng.standard_normal((2, 32, Vs)) * 0.1).astype(np.float32)
+        lg = np.stack([base[s, :, pos[s]: pos[s] + 32] + (rng.standard_normal((2, 32, Vs)) * (0.0 if flat else 0.1)).astype(np.float32)
                        for s in range(2)])
         ro, rg = o.step_from_logits(lg), g.step_from_logits(lg)
         assert ro == rg, (step, ro, rg)
