@@ -15,6 +15,7 @@
 // 64-bit uniform of the one draw made at `row`, word 3 = a fresh uniform draft.
 //
 // This translation unit must be compiled with -ffp-contract=off.
+#include <type_traits>
 #include "decide.h"
 
 #include "common.hip.h"
@@ -477,15 +478,46 @@ SJD_D uint64_t shfl_up_u64(uint64_t v, int delta) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-template <typename F>
-SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20] shared */) {
+// support(v): a cheap test that is true wherever weight(v) != 0 (may be true elsewhere).  With top-K most weights of
+// a row are 0 and the costly ones (the residual takes two double-precision divisions per id) are only evaluated
+// where the test holds: a thread marks its ids in a bit mask first, with unconditional batched loads, then walks
+// the marked ones - a few per thread instead of all.  The sums are integer sums, so nothing changes in the result.
+struct AnySupport { SJD_D bool operator()(int) const { return true; } };
+template <typename F, typename S = AnySupport>
+SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20] shared */, S support = S()) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6, nt = blockDim.x;
     // level 1: wavefront w owns the contiguous segment [w * seg, (w + 1) * seg), read 64 consecutive ids at a time
     const int per = (V + nt - 1) / nt;          // ids per thread at level 2
     const int seg = per * 64;
     const int v0 = wave * seg, v1 = v0 + seg < V ? v0 + seg : V;
     uint64_t local = 0;
-    for (int v = v0 + lane; v < v1; v += 64) local += weight(v);
+    if (!std::is_same<S, AnySupport>::value && per <= 64) {
+        uint64_t marked = 0;
+#pragma unroll 8
+        for (int i = 0; i < per; ++i) {
+            const int v = v0 + lane + 64 * i;
+            const bool sup = support(v < V ? v : V - 1);   // the load inside is unconditional
+            if (v < v1 && sup) marked |= 1ull << i;
+        }
+        while (marked) {
+            const int i = __builtin_ctzll(marked);
+            marked &= marked - 1ull;
+            local += weight(v0 + lane + 64 * i);
+        }
+    } else {
+        // batches of 8 ids with clamped, unconditional loads (a loop of load - add pays a memory round trip per id)
+        for (int i0 = 0; i0 < per; i0 += 8) {
+            uint64_t wv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int v = v0 + lane + 64 * (i0 + j);
+                wv[j] = weight(v < V ? v : V - 1);
+                if (v >= v1) wv[j] = 0;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) local += wv[j];
+        }
+    }
     for (int d = 32; d > 0; d >>= 1) local += shfl_down_u64(local, d);
     __syncthreads();
     if (lane == 0) sums[wave] = local;
@@ -610,7 +642,9 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
             double Q = rr == kRefOneHot ? (v == x ? 1.0 : 0.0) : prob(qrow ? weight_of(qrow[v]) : 1ull, Zq);
             return residual_weight(P, Q);
         };
-        tok = block_inverse_cdf(resid, V, u64, sums);
+        // p(v) has weight 0 below 2^-40 (weight_of), and where p is 0 so is max(0, p - q)
+        auto p_support = [&](int v) { return pk[v] >= 0x1p-40f; };
+        tok = block_inverse_cdf(resid, V, u64, sums, p_support);
         if (tok < 0) tok = block_inverse_cdf(from_p, V, u64, sums);
     } else if (k > a && k <= Le - 2) {
         const int x = d.win_tok[s * L + k + 1] - d.lo;
