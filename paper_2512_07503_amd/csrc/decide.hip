@@ -225,15 +225,25 @@ __global__ void sample_rows_kernel(SampleRowsArgs a) {
 // largest has that bit set, otherwise it does not and `want` drops by that count.  32 counting rounds of
 // wavefront ballots and one LDS exchange each, exact; after the first 10 bits the rounds run over the compacted
 // list of keys that still compete (see below).
-// adds one wave-uniform count per wavefront over the block; scratch alternates between rounds
+// adds one wave-uniform count per wavefront over a block of 16 wavefronts; scratch (16-byte aligned) alternates
+// between rounds.  The 16 counts come back as four 16-byte LDS reads: a round of the select is this exchange and
+// little else, and a loop of 16 dependent single reads made it twice as long.
 SJD_D uint32_t block_sum_wave_counts(uint32_t wave_count, uint32_t *scratch /* [16] */) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (lane == 0) scratch[wave] = wave_count;
     __syncthreads();
-    uint32_t t = 0;
-    for (int i = 0; i < nw; ++i) t += scratch[i];
-    return t;
+    const uint4 *q = reinterpret_cast<const uint4 *>(scratch);
+    const uint4 a = q[0], b = q[1], c = q[2], d = q[3];
+    return ((a.x + a.y) + (a.z + a.w)) + ((b.x + b.y) + (b.z + b.w)) + ((c.x + c.y) + (c.z + c.w)) + ((d.x + d.y) + (d.z + d.w));
 }
+
+// Wall-clock stamps of block 0 for probes (compiled out of the library)
+#ifdef SJD_PHASE_TIMING
+__device__ unsigned long long g_sample_phase[8];
+#define SJD_SAMPLE_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_sample_phase[i] = wall_clock64(); } while (0)
+#else
+#define SJD_SAMPLE_STAMP(i) do { } while (0)
+#endif
 
 template <int VPT>
 __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a) {
@@ -244,10 +254,12 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
     const uint32_t par = a.step ? (*a.step & 1u) : 0u;
     float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
     const int V = a.V, tid = threadIdx.x;
-    __shared__ uint32_t cnt[2][16], cnt2[16];
+    __shared__ __align__(16) uint32_t cnt[2][16];
+    __shared__ __align__(16) uint32_t cnt2[16];
     __shared__ uint32_t scratch32[17];
     __shared__ uint64_t scratch64[17];
 
+    SJD_SAMPLE_STAMP(0);
     uint32_t key[VPT];  // order key of the guided logit; 0 (below every real key) past the end of the row
     uint32_t kmax = 0;
     // The loads are unconditional (index clamped to the row) and issued in batches: a load under `if (v < V)` is
@@ -272,6 +284,7 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
     }
     kmax = block_max_u32(kmax, scratch32);
     const float m = key_to_float(kmax);
+    SJD_SAMPLE_STAMP(1);
 
     uint32_t thresh = 0;
     if (a.top_k < V) {
@@ -292,6 +305,7 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
         // over at most kCandPerThread keys per thread instead of VPT; otherwise the rounds go on over all keys.
         constexpr int kSplitBits = 10, kCandPerThread = 4, kCandMax = 1024 * kCandPerThread;
         for (int bit = 31; bit > 31 - kSplitBits; --bit) round_all(bit);
+        SJD_SAMPLE_STAMP(2);
         constexpr uint32_t top_mask = ~((1u << (32 - kSplitBits)) - 1u);
         __shared__ uint32_t cand[kCandMax];
         __shared__ uint32_t n_cand_lds;
@@ -306,6 +320,7 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
             for (int i = 0; i < VPT; ++i)
                 if ((key[i] & top_mask) == prefix) cand[atomicAdd(&n_cand_lds, 1u)] = key[i];
             __syncthreads();
+            SJD_SAMPLE_STAMP(3);
             uint32_t ck[kCandPerThread];
             bool cv[kCandPerThread];
 #pragma unroll
@@ -328,6 +343,7 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
         }
         thresh = prefix;
     }
+    SJD_SAMPLE_STAMP(4);
 
     uint64_t zsum = 0;
 #pragma unroll
@@ -340,8 +356,10 @@ __global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a)
             zsum += weight_of(ev);
         }
     }
+    SJD_SAMPLE_STAMP(5);
     zsum = block_sum_u64(zsum, scratch64);
     if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
+    SJD_SAMPLE_STAMP(6);
 }
 
 hipError_t launch_sample_rows_any(hipStream_t st, const SampleRowsArgs &a, int rows) {
