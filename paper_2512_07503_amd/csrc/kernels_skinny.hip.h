@@ -225,7 +225,7 @@ template <int MT, int NBW, int NW, int DEPTH, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(SkinnyArgs a) {
     const int tid = threadIdx.x;
     // computing workgroups come first: one per column group, or (row_split 2) two, listed per XCD like row groups
-    const int n_compute = SPLIT ? 16 * ((a.groups + 7) / 8) : a.groups;
+    const int n_compute = SPLIT ? 16 * ((a.groups + 7) / 8) : a.m_groups > 1 ? 8 * ((a.groups + 7) / 8) * a.m_groups : a.groups;
     if ((int)blockIdx.x >= n_compute && (a.pf_wgs | a.kv_wgs)) {  // whole workgroup: only touches what the next launches read
         if ((int)blockIdx.x < n_compute + a.pf_wgs) l2_warm_next(a, blockIdx.x, n_compute, tid, NW * 64);
         else l2_warm_kv(a, blockIdx.x, n_compute + a.pf_wgs, tid, NW * 64);
@@ -581,10 +581,10 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     constexpr int DEPTH = SJD_SKINNY_DEPTH;
     SkinnyArgs a = a_in;
     a.groups = groups;
-    if (a.m_groups > 1 || a.ksplit != 1) a.pf_wgs = a.kv_wgs = 0;
+    if (a.ksplit != 1) a.pf_wgs = a.kv_wgs = 0;
     if (a.row_split == 2 && (MT != 1 || a.m_groups > 1 || a.ksplit != 1 || EPI == EPI_PARTIAL)) return hipErrorInvalidValue;
-    const int n_compute = a.row_split == 2 ? 16 * ((groups + 7) / 8) : groups;
-    const dim3 grid(a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : n_compute + a.pf_wgs + a.kv_wgs, a.ksplit);
+    const int n_compute = a.row_split == 2 ? 16 * ((groups + 7) / 8) : a.m_groups > 1 ? 8 * ((groups + 7) / 8) * a.m_groups : groups;
+    const dim3 grid(n_compute + a.pf_wgs + a.kv_wgs, a.ksplit);
     constexpr bool kPair = EPI == EPI_QKV || EPI == EPI_SWIGLU;  // epilogues that need two column blocks
     if (nbw == 2) {
         if (MT == 1 && a.row_split == 2) gemm_skinny_kernel<1, 2, NW, DEPTH, EPI, true><<<grid, NW * 64, 0, st>>>(a);

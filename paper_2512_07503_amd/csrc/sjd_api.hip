@@ -348,15 +348,32 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     // and latency-bound: first touch from HBM costs 2-3x the time of an L2 hit, and the chip is mostly idle).
     struct Proj { const void *W; int groups, nbw, KB; bool whole; };
     const int groups_d = ceil_div(ceil_div(d, 32), nbw_d), groups_qkv = (H + 2 * Hkv) * (hd / 64);
-    auto resid_whole = [&](int K) { return (double)(nbw_d * 32 + MT * 32) * K * 2.0 <= 512e3; };
+    // More than 32 rows and so few column groups that a workgroup per group and 32-row tile still finds a CU of its
+    // own: row groups of 32 rows instead of 64 (all row groups of a column group on one XCD, whose L2 serves the
+    // later readers of the weights).  Each workgroup pulls half the activations, twice as many CUs work.
+    auto rows2_for = [&](int groups) {
+        return MT == 2 && 2 * m_groups * 8 * ceil_div(groups, 8) <= 256 && !(md.kernel_flags & SJD_NO_ROW_SPLIT);
+    };
+    // computing workgroups of a launch over `groups` column groups
+    auto compute_wgs = [&](int groups, bool r2, int row_split) {
+        if (r2) return 2 * m_groups * 8 * ceil_div(groups, 8);
+        if (row_split == 2) return 16 * ceil_div(groups, 8);
+        return m_groups > 1 ? m_groups * 8 * ceil_div(groups, 8) : groups;
+    };
+    const int mt_resid = rows2_for(groups_d) ? 1 : MT;   // 32-row tiles per workgroup of an output / down projection
+    auto resid_whole = [&](int K) { return (double)(nbw_d * 32 + mt_resid * 32) * K * 2.0 <= 512e3; };
     auto warm = [&](int cur_groups, const Proj &nx) {
         a.pf_wgs = 0;
-        if (!c->l2_warm || tile || m_groups > 1 || !nx.whole || !nx.W) return;
+        if (!c->l2_warm || tile || !nx.whole || !nx.W) return;
         const uint32_t slab = (uint32_t)nx.nbw * nx.KB * 1024;
-        const int fit = (int)std::min<size_t>(nx.groups, ((size_t)24 << 20) / slab);   // what the L2s hold beside the current weights
+        int fit = (int)std::min<size_t>(nx.groups, ((size_t)24 << 20) / slab);   // what the L2s hold beside the current weights
         int wgs = (int)(((size_t)fit * slab / (96 << 10) + 7) / 8 * 8);
         wgs = std::min(wgs, (256 - cur_groups) / 8 * 8);
-        if (wgs < 8 || fit < 1) return;
+        if (wgs < 8) return;
+        // few CUs left: touch no more than they get through while the launch computes (a CU streams ~45 GB/s from
+        // HBM, the launches take 7-10 us: 320 KB each), the first slabs
+        fit = (int)std::min<size_t>(fit, (size_t)wgs * (320 << 10) / slab);
+        if (fit < 1) return;
         a.pf_base = (const char *)nx.W; a.pf_slab_bytes = slab; a.pf_groups = fit; a.pf_wgs = wgs; a.pf_sink = c->pf_sink;
     };
     // The same for the keys and values of the next one-pass attention launch (one workgroup per (head, segment), in
@@ -409,7 +426,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             return SJD_OK;
         }
         const int groups = ceil_div(ceil_div(d, 32), nbw_d);
-        const double wg_bytes = (double)(nbw_d * 32 + MT * 32) * K * 2.0;
+        const double wg_bytes = (double)(nbw_d * 32 + mt_resid * 32) * K * 2.0;
         int ks = 1;
         if (wg_bytes > 512e3) {
             ks = std::min(8, std::max(1, 256 / (groups * m_groups)));
@@ -418,12 +435,15 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         if (ks == 1) {
             whole_k();
             a.row_split = row_split_for(groups);
-            const int n_compute = a.row_split == 2 ? 16 * ceil_div(groups, 8) : groups;
+            const bool r2 = rows2_for(groups);
+            a.m_groups = r2 ? 2 * m_groups : m_groups;
+            const int n_compute = compute_wgs(groups, r2, a.row_split);
             warm(n_compute, nx);
             if (kv_next) warm_kv(n_compute, *kv_next);
-            SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, MT, groups, nbw_d, nw_for(groups)));
+            SJD_LAUNCH(c, cls, launch_skinny<EPI_RESID>(st, a, r2 ? 1 : MT, groups, nbw_d, nw_for(groups)));
             a.pf_wgs = a.kv_wgs = 0;
             a.row_split = 1;
+            a.m_groups = m_groups;
             return SJD_OK;
         }
         a.kb_per_split = ceil_div(a.KB, ks);
@@ -453,12 +473,15 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         } else {
             whole_k();
             a.row_split = row_split_for(groups_qkv);
-            const int n_compute = a.row_split == 2 ? 16 * ceil_div(groups_qkv, 8) : groups_qkv;
+            const bool r2 = rows2_for(groups_qkv);
+            a.m_groups = r2 ? 2 * m_groups : m_groups;
+            const int n_compute = compute_wgs(groups_qkv, r2, a.row_split);
             warm(n_compute, Proj{lw.wo, groups_d, nbw_d, H * hd / 16, resid_whole(H * hd)});
             if (l == 0) warm_kv(n_compute, pool);  // later layers: requested by the down projection before them
-            SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, MT, groups_qkv, 2, nw_for(groups_qkv)));
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_skinny<EPI_QKV>(st, a, r2 ? 1 : MT, groups_qkv, 2, nw_for(groups_qkv)));
             a.pf_wgs = a.kv_wgs = 0;
             a.row_split = 1;
+            a.m_groups = m_groups;
         }
         { int rc = run_attention<bf16_t>(c, pool, M); if (rc) return rc; }
         { int rc = resid(KC_GEMM_O, c->attn, lw.wo, H * hd, Proj{lw.wgu, F / 32, 2, d / 16, true}, nullptr); if (rc) return rc; }
@@ -470,12 +493,15 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         } else {
             whole_k();
             a.row_split = row_split_for(F / 32);
-            const int n_compute = a.row_split == 2 ? 16 * ceil_div(F / 32, 8) : F / 32;
+            const bool r2 = rows2_for(F / 32);
+            a.m_groups = r2 ? 2 * m_groups : m_groups;
+            const int n_compute = compute_wgs(F / 32, r2, a.row_split);
             warm(n_compute, Proj{lw.wdown, groups_d, nbw_d, F / 16, resid_whole(F)});
             if (mixed_ok && skinny_mixed_applies(a, F / 32, 2, nw_for(F / 32))) SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny_mixed<EPI_SWIGLU>(st, a, MT, F / 32));
-            else SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, MT, F / 32, 2, nw_for(F / 32)));
+            else SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_skinny<EPI_SWIGLU>(st, a, r2 ? 1 : MT, F / 32, 2, nw_for(F / 32)));
             a.pf_wgs = 0;
             a.row_split = 1;
+            a.m_groups = m_groups;
         }
         const Proj after_down = l + 1 < md.n_layers ? Proj{c->layers[l + 1].wqkv, groups_qkv, 2, d / 16, true}
                                 : with_head         ? Proj{c->lm_head, ceil_div(ceil_div(c->Vs, 32), 2), 2, d / 16, true}
@@ -495,7 +521,12 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             whole_k();
             const int groups_v = ceil_div(ceil_div(c->Vs, 32), 2);
             if (mixed_ok && skinny_mixed_applies(a, groups_v, 2, nw_for(groups_v))) SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny_mixed<EPI_HEAD>(st, a, MT, groups_v));
-            else SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, MT, groups_v, 2, nw_for(groups_v)));
+            else {
+                const bool r2 = rows2_for(groups_v);
+                a.m_groups = r2 ? 2 * m_groups : m_groups;
+                SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, r2 ? 1 : MT, groups_v, 2, nw_for(groups_v)));
+                a.m_groups = m_groups;
+            }
         }
     }
     return SJD_OK;

@@ -69,6 +69,9 @@ def test_small_models_step_by_step(oracle, name, flags):
                                                    # windows longer than one 32-row attention tile: 48 (generic GEMMs),
                                                    # 64 (two row groups of the fused projections)
                                                    ("small_fused64", 48, None, None), ("small_fused64", 64, None, None),
+                                                   # 33..64 rows: two row groups of 32 per column group (24: 48 rows,
+                                                   # the second group half empty)
+                                                   ("small_fused64", 24, None, None), ("small_fused64", 32, None, None),
                                                    ("small_fused128", 96, None, None)])
 def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
     """The comparison modes of Sec. 5 run through the same step: L = 1 is plain autoregressive decoding, tau = inf is
@@ -134,6 +137,8 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
                                                               ("cfg2", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 3, 1, 0, None),
                                                               # ... with a single 32-row tile, and one group per workgroup
                                                               ("cfg2", 2, 64, 3, 1, 0, 12), ("cfg3", 2, 64, 2, 1, 256, None),
+                                                              # 64 rows on the narrow shape: every projection as two row groups
+                                                              ("cfg1", 2, 120, 4, 1, 0, 32), ("cfg3", 2, 64, 2, 1, 128, None),
                                                               ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None),
                                                               # the chunk + merge attention kernels the full-length
                                                               # 7B-class contexts use (these short twins would not)
