@@ -67,7 +67,9 @@ enum {
                                 * workgroup tiles (default: 128-row tiles where they
                                 * balance the CUs better)                              */
     SJD_NO_ROW_SPLIT = 128,    /* bf16, 17..32 rows: projections of at most 64 column groups
-                                * with one workgroup per group (default: two, 16 rows each) */
+                                * with one workgroup per group (default: two, 16 rows each);
+                                * more rows: 64-row groups also for projections of so few
+                                * column groups that 32-row groups would each get a CU     */
     SJD_NO_MIXED_WIDTH = 256,  /* bf16, <= 64 rows: gate/up and head projections of more than
                                 * 256 column groups with one workgroup per group (default:
                                 * one workgroup per CU, some of them two groups wide)   */
