@@ -87,6 +87,22 @@ def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
     print(name, window, tau, top_k, "steps", steps, "worst logits error abs/rel:", worst)
 
 
+@pytest.mark.parametrize("name,n_seqs,window,flags", [("small_fused64", 2, None, 0), ("small_fused64", 2, None, 128),
+                                                       ("small_fused64", 3, 8, 0), ("small_fused64", 4, 16, 0)])
+def test_several_sequences_in_the_row_groups(oracle, name, n_seqs, window, flags):
+    """Sequences of different lengths share a forward: 2 x 16-token windows fill two row groups of 32 rows (one of 64
+    with flag 128), 3 x 8 leave the second group half empty, 4 x 16 = 128 rows take the generic GEMMs; each sequence
+    keeps its own accept length and page table."""
+    cfg = workload.get_config(name)
+    n_image = [40, 23, 31, 12][:n_seqs]
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, n_seqs=n_seqs, window=window, n_image=n_image, kernel_flags=flags,
+                                          head_alpha=6.0, std=0.08)
+    worst, steps = _lockstep(o, g, n_seqs, 200, tol_rel=8e-2)
+    for s in range(n_seqs):
+        assert len(g.tokens(s)) == n_img[s]
+    print(name, n_seqs, window, flags, "steps", steps, "worst logits error abs/rel:", worst)
+
+
 @pytest.mark.parametrize("name,mode,row_width,tau", [("small_f32", 1, 0, None), ("small_f32", 2, 3, None), ("small_f32", 2, 12, None),
                                                      ("small_f32", 3, 0, None), ("small_sub", 1, 0, float("inf")),
                                                      ("small_sub", 2, 2, None), ("small_sub", 3, 0, 0.0),
