@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=0, help="oracle steps in the CPU baseline (0 = sized to ~20 s)")
     ap.add_argument("--kernel-flags", type=int, default=0)
+    ap.add_argument("--n-seqs", type=int, default=0, help="override the configuration's number of prompts decoded together")
     ap.add_argument("--window", type=int, default=0, help="override the configuration's Jacobi window L (1 = plain autoregressive decoding)")
     ap.add_argument("--tau", type=float, default=None, help="override the reuse threshold (inf = SJD without token reuse, Eq. 6)")
     ap.add_argument("--top-k", type=int, default=0, help="override top-K (1 = greedy Jacobi decoding)")
@@ -93,6 +94,7 @@ def main():
         del src, dst
     cfg = workload.get_config(args.config)
     if args.window: cfg["window"] = args.window
+    if args.n_seqs: cfg["n_seqs"] = args.n_seqs
     if args.tau is not None: cfg["tau"] = args.tau
     if args.top_k: cfg["top_k"] = args.top_k
     arch, L, S, N, P = cfg["arch"], cfg["window"], cfg["n_seqs"], cfg["n_image"], cfg["prompt_len"]
