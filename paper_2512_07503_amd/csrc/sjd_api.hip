@@ -369,7 +369,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         int fit = (int)std::min<size_t>(nx.groups, ((size_t)24 << 20) / slab);   // what the L2s hold beside the current weights
         int wgs = (int)(((size_t)fit * slab / (96 << 10) + 7) / 8 * 8);
         wgs = std::min(wgs, (256 - cur_groups) / 8 * 8);
-        if (wgs < 8) return;
+        if (wgs < 8 || (m_groups > 1 && wgs < 32)) return;   // long-window launches: a handful of CUs only delays them
         // few CUs left: touch no more than they get through while the launch computes (a CU streams ~45 GB/s from
         // HBM, the launches take 7-10 us: 320 KB each), the first slabs
         fit = (int)std::min<size_t>(fit, (size_t)wgs * (320 << 10) / slab);
