@@ -241,6 +241,18 @@ int sjd_trace_read(sjd_ctx *ctx, sjd_trace_entry *dst, int32_t cap, int32_t *n_o
 int sjd_op_gemm(void *hip_stream, int32_t dtype, int32_t flags, const void *A, const void *W, float *C, int32_t M,
                 int32_t N, int32_t K, int32_t splits, int32_t repeat, float *avg_ms);
 
+/* sjd_op_gemm for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels,
+ * with the temporaries (both operands re-laid-out for the kernels and the split-K
+ * partial sums) in a 32 MiB workspace that is part of the library image on every
+ * device.  The call allocates nothing, creates no events and returns after completion.
+ * SJD_ECAPACITY when the temporaries of M x N x K exceed the workspace
+ * (bf16: 2 (ceil32(M) + ceil32(N)) K + 4 splits M N bytes, each part rounded up to 256).
+ * All calls on one device share the workspace: calls that overlap on one device
+ * (different streams or threads) race; serialise them. */
+int sjd_op_gemm_static(void *hip_stream, int32_t dtype, int32_t flags, const void *A, const void *W, float *C, int32_t M,
+                       int32_t N, int32_t K, int32_t splits);
+
 /* Window attention of one (sequence, branch): q [n][H][hd], k and v
  * [ctx + n][Hkv][hd] of `dtype` (the first ctx positions are the cache, the
  * last n the window), out [n][H][hd] fp32.  Query i sees positions

@@ -78,6 +78,8 @@ def lib():
         L.sjd_trace_read.argtypes = [C.c_void_p, C.POINTER(TraceEntry), C.c_int32, IP]
         L.sjd_op_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+        L.sjd_op_gemm_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.c_int32, C.c_int32, C.c_int32]
         L.sjd_op_window_attention.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                               C.c_int32, C.c_int32, C.POINTER(C.c_float)]
@@ -256,6 +258,17 @@ def op_gemm(A, W, flags=0, splits=0, repeat=1):
     _check(lib().sjd_op_gemm(_stream_ptr(), _dtype_code(A), flags, A.data_ptr(), W.data_ptr(), Cout.data_ptr(), M, N, K,
                              splits, repeat, C.byref(ms)))
     return Cout, ms.value
+
+
+def op_gemm_static(A, W, flags=0, splits=0):
+    """C = A @ W.T through sjd_op_gemm_static (no allocation inside the library); returns the status code and C."""
+    import torch
+    M, K = A.shape
+    N = W.shape[0]
+    Cout = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    rc = lib().sjd_op_gemm_static(_stream_ptr(), _dtype_code(A), flags, A.data_ptr(), W.data_ptr(), Cout.data_ptr(), M, N, K,
+                                  splits)
+    return rc, Cout
 
 
 def op_window_attention(q, k, v, ctx, page_tokens=64, flags=0, repeat=1):

@@ -32,39 +32,110 @@ struct Scratch {
         }                                                                                             \
     } while (0)
 
+// Bytes of the three temporaries of a GEMM call, each rounded up to 256: the two operands in the kernels' layout and the
+// split-K partial sums [splits][M][N] that the GEMM kernel writes and reduce_partials_kernel adds up.
+struct GemmTemps { size_t a_bytes, w_bytes, part_bytes; int n_splits; GemmPlan plan; bool ref; };
+template <typename T> GemmTemps gemm_temps(int flags, int M, int N, int K, int splits) {
+    GemmTemps t;
+    t.ref = std::is_same<T, float>::value || (flags & SJD_KERNELS_REFERENCE);
+    t.plan = GemmPlan{};
+    if (!t.ref) t.plan = plan_gemm_bf16(M, N, K, splits);   // bf16: K is a positive multiple of 16 (checked by the entry points)
+    t.n_splits = t.ref ? 1 : t.plan.splits;
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    t.a_bytes = up(Layout<T>::a_elems(M, K) * sizeof(T));
+    t.w_bytes = up(Layout<T>::w_elems(N, K) * sizeof(T));
+    t.part_bytes = up((size_t)t.n_splits * M * N * sizeof(float));
+    return t;
+}
+
+// The launches of a GEMM call on temporaries the caller provides; ev0 / ev1 (may be null) bracket the GEMM launches.
+template <typename T>
+int gemm_on_temps(hipStream_t st, const GemmTemps &t, const void *A, const void *W, float *C, T *Ap, T *Wp, float *partial, int M,
+                  int N, int K, int repeat, hipEvent_t ev0, hipEvent_t ev1) {
+    pack_act_kernel<T><<<512, 256, 0, st>>>((const T *)A, Ap, M, K);
+    OP_TRY(hipGetLastError());
+    pack_weight_kernel<T><<<1024, 256, 0, st>>>((const T *)W, Wp, N, K, 0);
+    OP_TRY(hipGetLastError());
+    if (ev0) OP_TRY(hipEventRecord(ev0, st));
+    for (int r = 0; r < repeat; ++r) {
+        if (t.ref) OP_TRY(launch_gemm_reference<T>(st, Ap, Wp, partial, M, N, K));
+        else OP_TRY(launch_gemm_bf16(st, t.plan, (const bf16_t *)Ap, (const bf16_t *)Wp, partial, M, N, K));
+    }
+    if (ev1) OP_TRY(hipEventRecord(ev1, st));
+    reduce_partials_kernel<<<(unsigned)ceil_div_sz((size_t)M * N, 256), 256, 0, st>>>(partial, t.n_splits, (size_t)M * N, C);
+    OP_TRY(hipGetLastError());
+    OP_TRY(hipStreamSynchronize(st));
+    return SJD_OK;
+}
+
 template <typename T>
 int op_gemm(hipStream_t st, int flags, const void *A, const void *W, float *C, int M, int N, int K, int splits, int repeat,
             float *avg_ms) {
     Scratch s;
     T *Ap, *Wp;
     float *partial;
-    const bool ref = std::is_same<T, float>::value || (flags & SJD_KERNELS_REFERENCE);
-    GemmPlan plan = plan_gemm_bf16(M, N, K, splits);
-    const int n_splits = ref ? 1 : plan.splits;
-    if (!s.alloc(&Ap, Layout<T>::a_elems(M, K) * sizeof(T), st) || !s.alloc(&Wp, Layout<T>::w_elems(N, K) * sizeof(T), st) ||
-        !s.alloc(&partial, (size_t)n_splits * M * N * sizeof(float), st) || !s.events()) {
+    const GemmTemps t = gemm_temps<T>(flags, M, N, K, splits);
+    if (!s.alloc(&Ap, t.a_bytes, st) || !s.alloc(&Wp, t.w_bytes, st) || !s.alloc(&partial, t.part_bytes, st) || !s.events()) {
         sjd_set_error(g_create_error, "allocation failed");
         return SJD_ENOMEM;
     }
-    pack_act_kernel<T><<<512, 256, 0, st>>>((const T *)A, Ap, M, K);
-    OP_TRY(hipGetLastError());
-    pack_weight_kernel<T><<<1024, 256, 0, st>>>((const T *)W, Wp, N, K, 0);
-    OP_TRY(hipGetLastError());
-    OP_TRY(hipEventRecord(s.ev0, st));
-    for (int r = 0; r < repeat; ++r) {
-        if (ref) OP_TRY(launch_gemm_reference<T>(st, Ap, Wp, partial, M, N, K));
-        else OP_TRY(launch_gemm_bf16(st, plan, (const bf16_t *)Ap, (const bf16_t *)Wp, partial, M, N, K));
-    }
-    OP_TRY(hipEventRecord(s.ev1, st));
-    reduce_partials_kernel<<<(unsigned)ceil_div_sz((size_t)M * N, 256), 256, 0, st>>>(partial, n_splits, (size_t)M * N, C);
-    OP_TRY(hipGetLastError());
-    OP_TRY(hipStreamSynchronize(st));
+    const int rc = gemm_on_temps<T>(st, t, A, W, C, Ap, Wp, partial, M, N, K, repeat, s.ev0, s.ev1);
+    if (rc) return rc;
     if (avg_ms) {
         float ms = 0.0f;
         OP_TRY(hipEventElapsedTime(&ms, s.ev0, s.ev1));
         *avg_ms = ms / repeat;
     }
     return SJD_OK;
+}
+
+// ---- the same call without any allocation: its temporaries live in a file-scope device array.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// In host code the name `scratch` is only a handle of the symbol; the array's address on a device comes from
+// hipGetSymbolAddress, once per device (every device holds its own copy at its own address).
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+int static_scratch(unsigned char **out) {
+    int dev = -1;
+    OP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { sjd_set_error(g_create_error, "device index %d out of range", dev); return SJD_EDEVICE; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        OP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { sjd_set_error(g_create_error, "hipGetSymbolAddress returned a null address"); return SJD_EDEVICE; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (unsigned char *)g_scratch_ptr[dev];
+    return SJD_OK;
+}
+
+__global__ void zero_fill_kernel(u32x4 *p, size_t n16) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
+}
+
+template <typename T>
+int op_gemm_static(hipStream_t st, int flags, const void *A, const void *W, float *C, int M, int N, int K, int splits) {
+    const GemmTemps t = gemm_temps<T>(flags, M, N, K, splits);
+    const size_t need = t.a_bytes + t.w_bytes + t.part_bytes;
+    if (need > kStaticScratchBytes) {
+        sjd_set_error(g_create_error, "sjd_op_gemm_static: %d x %d x %d needs %zu bytes of temporaries, the static workspace holds %zu",
+                      M, N, K, need, kStaticScratchBytes);
+        return SJD_ECAPACITY;
+    }
+    unsigned char *base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc) return rc;
+    // The workspace keeps the last call's contents.  The operand copies are padded to whole 32-row fragments and the pack
+    // kernels write the real rows only: clear both (a fill kernel, not a memset node, so that the call can be captured).
+    zero_fill_kernel<<<256, 256, 0, st>>>((u32x4 *)base, (t.a_bytes + t.w_bytes) / 16);
+    OP_TRY(hipGetLastError());
+    return gemm_on_temps<T>(st, t, A, W, C, (T *)base, (T *)(base + t.a_bytes), (float *)(base + t.a_bytes + t.w_bytes), M, N, K, 1,
+                            nullptr, nullptr);
 }
 
 template <typename T>
@@ -140,6 +211,18 @@ int sjd_op_gemm(void *hip_stream, int32_t dtype, int32_t flags, const void *A, c
     if (dtype == SJD_BF16) {
         if (K % 16) { sjd_set_error(g_create_error, "bf16 GEMM needs K %% 16 == 0"); return SJD_EINVAL; }
         return op_gemm<bf16_t>((hipStream_t)hip_stream, flags, A, W, C, M, N, K, splits, repeat, avg_ms);
+    }
+    sjd_set_error(g_create_error, "unknown dtype");
+    return SJD_EINVAL;
+}
+
+int sjd_op_gemm_static(void *hip_stream, int32_t dtype, int32_t flags, const void *A, const void *W, float *C, int32_t M,
+                       int32_t N, int32_t K, int32_t splits) {
+    if (!A || !W || !C || M < 1 || N < 1 || K < 1) { sjd_set_error(g_create_error, "bad argument"); return SJD_EINVAL; }
+    if (dtype == SJD_F32) return op_gemm_static<float>((hipStream_t)hip_stream, flags, A, W, C, M, N, K, splits);
+    if (dtype == SJD_BF16) {
+        if (K % 16) { sjd_set_error(g_create_error, "bf16 GEMM needs K %% 16 == 0"); return SJD_EINVAL; }
+        return op_gemm_static<bf16_t>((hipStream_t)hip_stream, flags, A, W, C, M, N, K, splits);
     }
     sjd_set_error(g_create_error, "unknown dtype");
     return SJD_EINVAL;

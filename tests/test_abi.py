@@ -63,6 +63,20 @@ def test_null_context_calls_are_errors_not_crashes():
     L.sjd_destroy(None)
     assert L.sjd_op_gemm(None, 1, 0, None, None, None, 1, 1, 16, 0, 1, None) == sjd.binding.EINVAL
     assert L.sjd_op_philox(None, 0, 0, 0, None, 4) == sjd.binding.EINVAL
+    assert L.sjd_op_gemm_static(None, 1, 0, None, None, None, 1, 1, 16, 0) == sjd.binding.EINVAL
+
+
+def test_static_gemm_rejects_what_does_not_fit_before_touching_a_device():
+    """The no-allocation GEMM holds its temporaries in a 32 MiB workspace: sizes beyond it are refused on the host
+    (dummy non-null pointers: nothing may be dereferenced or launched)."""
+    import paper_2512_07503_amd as sjd
+    L = sjd.lib()
+    one = C.c_void_p(1)
+    assert L.sjd_op_gemm_static(None, 1, 0, one, one, one, 512, 65536, 4096, 0) == sjd.binding.ECAPACITY
+    assert b"static workspace" in L.sjd_last_error(None)
+    assert L.sjd_op_gemm_static(None, 0, 0, one, one, one, 4096, 4096, 4096, 0) == sjd.binding.ECAPACITY
+    assert L.sjd_op_gemm_static(None, 1, 0, one, one, one, 32, 64, 24, 0) == sjd.binding.EINVAL   # bf16: K % 16
+    assert L.sjd_op_gemm_static(None, 9, 0, one, one, one, 32, 64, 32, 0) == sjd.binding.EINVAL
 
 
 def test_the_product_does_not_reach_into_the_oracle():
