@@ -148,6 +148,11 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
 
 
 @pytest.mark.parametrize("name,layers,prompt,steps,S,flags,window", [("cfg1", 36, 24, 3, 1, 0, None), ("cfg1", 2, 120, 40, 1, 0, None),
+                                                              # norm gains drawn from U(0.5, 1.5) (flag bit 1 << 20 of this
+                                                              # table only: not a kernel flag): the fused kernels fold
+                                                              # the gain into the packed weights, one more rounding
+                                                              ("cfg1", 2, 120, 6, 1, 1 << 20, None), ("cfg2", 2, 64, 3, 1, 1 << 20, None),
+                                                              ("cfg3", 2, 64, 3, 1, 1 << 20, None), ("cfg4", 2, 64, 2, 5, 1 << 20, None),
                                                               # gate/up and head of the 7B shapes: workgroups of two widths
                                                               # (344 groups: 88 wide + 168; 448: 192 + 64; heads: all wide)
                                                               ("cfg2", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 3, 1, 0, None),
@@ -169,9 +174,9 @@ def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags, wi
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
     cfg = workload.get_config(name)
     arch = dict(cfg["arch"], n_layers=layers)
-    w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16")
+    w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16", random_gains=bool(flags & (1 << 20)))
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S, window=window,
-                                          n_image=min(cfg["n_image"], 200), kernel_flags=flags)
+                                          n_image=min(cfg["n_image"], 200), kernel_flags=flags & 0xFFFF)
     worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)
     print(name, layers, "worst logits error abs/rel:", worst)
 

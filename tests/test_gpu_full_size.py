@@ -1,19 +1,10 @@
 """The 7B-class benchmark shapes at full depth, width, vocabulary and batch, in the launch configuration bench.py
-times (fused / tile kernels, replayed graph).
-
-The double-precision oracle needs hours for one forward of these models, so the reference here is the library's own
-fp32 mode (plain fp32 kernels, no bf16 anywhere; test_gpu_e2e.py holds it to the oracle at 1e-4 on small shapes and
-at the cfg0 shape) run on the same bf16-valued weights, and what is checked are properties that hold at any size:
-  * the first decoding step's logits of the bf16 fused path stay within what bf16 activations cost at this depth.
-    A rounding point costs 2^-9 relative, a layer has about six (projection inputs, queries / keys / values,
-    probabilities, attention output, MLP hidden), and the errors add in quadrature: sqrt(6 x 32) x 2^-9 = 2.7e-2
-    before the model amplifies them.  Measured at 32 layers: 4.5e-2 - 5.0e-2 of a row's largest |logit| (1.0e-2 at
-    2 layers, 1.9e-2 at 8: the square-root growth), so the 3e-2 that the depth-reduced twins and the 36-layer cfg1
-    shape are held to is out of reach of the format here; the bound is 6e-2;
-  * the fused path is no further from fp32 than an independent bf16 implementation of the same forward, the plain
-    reference kernels (`KERNELS_REFERENCE`: no MFMA, separate normalisation / rotary / SwiGLU kernels), which
-    measure 5.5e-2 - 6.1e-2: the distance is the format's, not the kernels';
-  * a step is reproducible bit for bit (restore the state saved before it and run it again), verdicts included.
+times (fused / tile kernels, replayed graph): properties that hold at any size.  (The comparison of these shapes
+with the oracle at full depth, and the stated tolerance, are in test_gpu_full_depth_oracle.py.)
+  * a step is reproducible bit for bit (restore the state saved before it and run it again), verdicts included;
+  * the fused path is no further from the library's fp32 mode (plain fp32 kernels on the same bf16-valued weights) than
+    an independent bf16 implementation of the same forward, the plain reference kernels (`KERNELS_REFERENCE`: no
+    MFMA, separate normalisation / rotary / SwiGLU kernels): its distance is the storage format's, not the kernels'.
 Decisions at these vocabulary sizes are compared with the oracle in test_gpu_decide.py.
 """
 import numpy as np
@@ -64,5 +55,4 @@ def test_full_size_step_against_the_fp32_path(name, S):
     want = f.logits()
     err_fused, err_plain = logits_error(got, want, les), logits_error(plain, want, les)
     print(name, "worst |d| / max|logit| of a row against fp32: fused", err_fused[1], "plain bf16 kernels", err_plain[1])
-    assert err_fused[1] <= 6e-2, err_fused
     assert err_fused[1] <= 1.1 * err_plain[1], (err_fused, err_plain)
