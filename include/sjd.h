@@ -182,6 +182,19 @@ int sjd_get_tokens(sjd_ctx *ctx, int32_t seq, int32_t *dst, int32_t cap, int32_t
  * that is its reference distribution (-1 = uniform); *n_slots = slots in use. */
 int sjd_get_window(sjd_ctx *ctx, int32_t seq, int32_t *tokens, int32_t *ref_rows, int32_t *n_slots);
 
+/* Forced tokens (structure tokens of an image grammar, such as the end-of-row
+ * token that closes every row of a 48 x 49 token image): image position i of
+ * sequence `seq` may only take ids in [first_id[i], end_id[i]), i < n_positions
+ * (HOST arrays; absolute ids inside [sample_lo, sample_hi)).  Ids outside the
+ * range get probability 0 at that position before top-K (Sec. 3.1) is applied,
+ * so a range of one id forces that token.  Drafts are still initialised over all
+ * sampled ids; one that falls outside its position's range has p = 0 and is
+ * rejected by Eq. 2 with certainty.  Call after sjd_prefill (which resets every
+ * position to the whole sampled range); positions >= n_positions keep theirs.
+ * Errors: SJD_ESTATE (no prefill), SJD_EINVAL (bad index, empty range, range
+ * outside the sampled ids, n_positions > image tokens of the sequence). */
+int sjd_set_token_ranges(sjd_ctx *ctx, int32_t seq, const int32_t *first_id, const int32_t *end_id, int32_t n_positions);
+
 const char *sjd_last_error(const sjd_ctx *ctx);
 
 /* fp32 logits of the last step, [n_seqs][2 (cond, uncond)][window][V_s],
@@ -262,11 +275,16 @@ int sjd_op_window_attention(void *hip_stream, int32_t dtype, int32_t flags, cons
                             int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens, int32_t repeat,
                             float *avg_ms);
 
-/* Sampling distribution of `rows` positions: logits_c / logits_u [rows][V]
- * fp32 -> e [rows][V] fp32 softmax weights (0 outside the top-k set) and
- * Z [rows] uint64 integer normalisers. */
+/* Sampling distribution of `rows` positions (Sec. 3.1 top-K sampling with the
+ * guidance weight of Sec. 5.1): logits_c / logits_u [rows][V] fp32 -> e [rows][V]
+ * fp32 softmax weights (0 outside the top-k set) and Z [rows] uint64 integer
+ * normalisers.  allow_lo / allow_hi (DEVICE [rows], both or neither NULL): row r
+ * may only keep ids in [allow_lo[r], allow_hi[r]).  kept_ids [rows][V] and
+ * kept_cnt [rows] (DEVICE, may be NULL) receive the form in which the decoder
+ * stores a row: the ids with a weight, ascending, and their number. */
 int sjd_op_sampling_rows(void *hip_stream, const float *logits_c, const float *logits_u, float *e, uint64_t *Z,
                          int32_t rows, int32_t V, float cfg_scale, float temperature, int32_t top_k,
+                         const int32_t *allow_lo, const int32_t *allow_hi, int32_t *kept_ids, int32_t *kept_cnt,
                          int32_t repeat, float *avg_ms);
 
 /* out[4*i .. 4*i+3] = Philox4x32-10(counter = (i, row, seq, 0), key = seed), i < n. */

@@ -58,6 +58,7 @@ typedef struct {
     int32_t cond_len, uncond_len, n_image;
     int32_t n_img; /* image tokens final so far */
     int32_t *out;  /* [n_image] */
+    int32_t *allow_lo, *allow_hi; /* [n_image] ids (relative to sample_lo) image position i may take: [lo, hi) */
     int32_t anchor[2];
     int32_t *tok;     /* [L] window tokens, slot 0 unused (anchor above) */
     int32_t *ref_row; /* [L] slot -> row of `ref_e` that is its reference, -1 = uniform, -2 = one-hot at the draft,
@@ -94,7 +95,7 @@ int oracle_set_num_threads(int32_t n) {
 }
 
 static void seq_release(seq_state *s) {
-    free(s->out); free(s->tok); free(s->ref_row); free(s->ref_e); free(s->ref_Z); free(s->hist_e); free(s->hist_Z);
+    free(s->out); free(s->allow_lo); free(s->allow_hi); free(s->tok); free(s->ref_row); free(s->ref_e); free(s->ref_Z); free(s->hist_e); free(s->hist_Z);
     oracle_cache_free(s->cache[0]);
     oracle_cache_free(s->cache[1]);
     memset(s, 0, sizeof *s);
@@ -162,6 +163,10 @@ int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids
         seq_state *q = &c->seq[s];
         q->cond_len = cond_len[s]; q->uncond_len = uncond_len[s]; q->n_image = n_image_tokens[s];
         q->out = (int32_t *)calloc((size_t)q->n_image, sizeof(int32_t));
+        q->allow_lo = (int32_t *)calloc((size_t)q->n_image, sizeof(int32_t));
+        q->allow_hi = (int32_t *)calloc((size_t)q->n_image, sizeof(int32_t));
+        if (!q->allow_lo || !q->allow_hi) return ENOMEM_;
+        for (int i = 0; i < q->n_image; ++i) q->allow_hi[i] = c->Vs;   /* no forced tokens until the caller sets some */
         q->tok = (int32_t *)calloc((size_t)c->L, sizeof(int32_t));
         q->ref_row = (int32_t *)calloc((size_t)c->L, sizeof(int32_t));
         q->ref_e = (float *)calloc((size_t)c->L * c->Vs, sizeof(float));
@@ -195,6 +200,20 @@ int oracle_prefill(oracle_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids
         }
     }
     c->prefilled = 1;
+    return OK;
+}
+
+int oracle_set_token_ranges(oracle_ctx *c, int32_t seq, const int32_t *first_id, const int32_t *end_id,
+                            int32_t n_positions) {
+    if (!c || !first_id || !end_id) return EINVAL_;
+    if (!c->prefilled) return ESTATE_;
+    if (seq < 0 || seq >= c->n_seqs || n_positions < 0 || n_positions > c->seq[seq].n_image) return EINVAL_;
+    for (int i = 0; i < n_positions; ++i)
+        if (first_id[i] < c->md.sample_lo || end_id[i] > c->md.sample_hi || first_id[i] >= end_id[i]) return EINVAL_;
+    for (int i = 0; i < n_positions; ++i) {
+        c->seq[seq].allow_lo[i] = first_id[i] - c->md.sample_lo;
+        c->seq[seq].allow_hi[i] = end_id[i] - c->md.sample_lo;
+    }
     return OK;
 }
 
@@ -378,9 +397,10 @@ static int step_impl(oracle_ctx *c, const float *given_logits, oracle_step_resul
             int rc = forward_current(c, s, Le);
             if (rc) return rc;
         }
-        for (int k = 0; k < Le; ++k)
-            oracle_sampling_row(lg + (size_t)k * Vs, lg + (size_t)(L + k) * Vs, Vs, c->sp.cfg_scale,
-                                c->sp.temperature, c->sp.top_k, c->new_e + (size_t)k * Vs, &c->new_Z[k]);
+        for (int k = 0; k < Le; ++k) /* row k is the distribution of image position n_img + k */
+            oracle_sampling_row_range(lg + (size_t)k * Vs, lg + (size_t)(L + k) * Vs, Vs, c->sp.cfg_scale,
+                                      c->sp.temperature, c->sp.top_k, q->allow_lo[q->n_img + k], q->allow_hi[q->n_img + k],
+                                      c->new_e + (size_t)k * Vs, &c->new_Z[k]);
         decide(c, s, Le, res);
     }
     return OK;

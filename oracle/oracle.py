@@ -55,9 +55,14 @@ def lib():
         L.oracle_keep.argtypes = [C.c_float, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64]
         L.oracle_draw.argtypes = [_FP, C.c_uint64, C.c_int32, C.c_uint64]
         L.oracle_draw_residual.argtypes = [_FP, C.c_uint64, _FP, C.c_uint64, C.c_int32, C.c_uint64]
+        L.oracle_draw_residual_onehot.argtypes = [_FP, C.c_uint64, C.c_int32, C.c_int32, C.c_uint64]
         L.oracle_sampling_row.argtypes = [_FP, _FP, C.c_int32, C.c_float, C.c_float, C.c_int32, _FP,
                                           C.POINTER(C.c_uint64)]
         L.oracle_sampling_row.restype = None
+        L.oracle_sampling_row_range.argtypes = [_FP, _FP, C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.c_int32, _FP,
+                                                C.POINTER(C.c_uint64)]
+        L.oracle_sampling_row_range.restype = None
+        L.oracle_set_token_ranges.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32]
         L.oracle_law_trials.argtypes = [_FP, C.c_uint64, _FP, C.c_uint64, C.c_int32, C.c_uint64, C.c_int64,
                                         C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.oracle_law_trials.restype = None
@@ -116,13 +121,18 @@ def weight_of(e):
     return int(lib().oracle_weight_of(C.c_float(e)))
 
 
-def sampling_row(logit_c, logit_u, cfg_scale, temperature, top_k):
+def sampling_row(logit_c, logit_u, cfg_scale, temperature, top_k, allow=None):
+    """allow = (lo, hi): only ids in [lo, hi) of the row can have weight (forced-token mask)."""
     lc = np.ascontiguousarray(logit_c, dtype=np.float32)
     lu = np.ascontiguousarray(logit_u, dtype=np.float32)
     V = lc.shape[0]
     e = np.zeros(V, dtype=np.float32)
     Z = C.c_uint64(0)
-    lib().oracle_sampling_row(_fp(lc), _fp(lu), V, cfg_scale, temperature, top_k, _fp(e), C.byref(Z))
+    if allow is None:
+        lib().oracle_sampling_row(_fp(lc), _fp(lu), V, cfg_scale, temperature, top_k, _fp(e), C.byref(Z))
+    else:
+        assert 0 <= allow[0] < allow[1] <= V
+        lib().oracle_sampling_row_range(_fp(lc), _fp(lu), V, cfg_scale, temperature, top_k, allow[0], allow[1], _fp(e), C.byref(Z))
     return e, int(Z.value)
 
 
@@ -149,6 +159,11 @@ def draw_residual(e_p, Z_p, e_q, Z_q, u64):
         return int(lib().oracle_draw_residual(_fp(ep), Z_p, None, 0, ep.shape[0], u64))
     eq = np.ascontiguousarray(e_q, dtype=np.float32)
     return int(lib().oracle_draw_residual(_fp(ep), Z_p, _fp(eq), Z_q, ep.shape[0], u64))
+
+
+def draw_residual_onehot(e_p, Z_p, x, u64):
+    ep = np.ascontiguousarray(e_p, dtype=np.float32)
+    return int(lib().oracle_draw_residual_onehot(_fp(ep), Z_p, x, ep.shape[0], u64))
 
 
 def law_trials(e_p, Z_p, e_q, Z_q, seed, n_trials):
@@ -277,6 +292,12 @@ class Oracle:
         if rc == 0:
             self.n_seqs = S
         return rc
+
+    def set_token_ranges(self, seq, first_id, end_id):
+        lo = np.ascontiguousarray(first_id, dtype=np.int32)
+        hi = np.ascontiguousarray(end_id, dtype=np.int32)
+        assert lo.shape == hi.shape and lo.ndim == 1
+        return lib().oracle_set_token_ranges(self.ctx, seq, _ip(lo), _ip(hi), len(lo))
 
     def _results(self, arr):
         return [dict(n_accepted=r.n_accepted, n_finalized=r.n_finalized, reject_index=r.reject_index,

@@ -72,28 +72,38 @@ static int cmp_float_desc(const void *a, const void *b) {
 }
 
 /* Guidance on raw logits z = l_u + s (l_c - l_u), times 1/T, then top-K with
- * ties at the K-th value kept, then softmax weights relative to the maximum. */
-void oracle_sampling_row(const float *logit_c, const float *logit_u, int32_t V, float cfg_scale,
-                         float temperature, int32_t top_k, float *e, uint64_t *Z) {
+ * ties at the K-th value kept, then softmax weights relative to the maximum.
+ * Only ids in [allow_lo, allow_hi) are candidates (a forced-token mask: every
+ * other id has probability 0, as if its logit were minus infinity). */
+void oracle_sampling_row_range(const float *logit_c, const float *logit_u, int32_t V, float cfg_scale,
+                               float temperature, int32_t top_k, int32_t allow_lo, int32_t allow_hi, float *e,
+                               uint64_t *Z) {
     float inv_t = 1.0f / temperature;
+    int32_t n = allow_hi - allow_lo;
     float *z = (float *)malloc(sizeof(float) * (size_t)V);
-    float *sorted = (float *)malloc(sizeof(float) * (size_t)V);
+    float *sorted = (float *)malloc(sizeof(float) * (size_t)n);
     for (int32_t v = 0; v < V; ++v) {
         float d = logit_c[v] - logit_u[v];
         z[v] = fmaf(cfg_scale, d, logit_u[v]) * inv_t;
     }
-    memcpy(sorted, z, sizeof(float) * (size_t)V);
-    qsort(sorted, (size_t)V, sizeof(float), cmp_float_desc);
+    memcpy(sorted, z + allow_lo, sizeof(float) * (size_t)n);
+    qsort(sorted, (size_t)n, sizeof(float), cmp_float_desc);
     float m = sorted[0];
-    float t = (top_k >= V) ? sorted[V - 1] : sorted[top_k - 1];
+    float t = (top_k >= n) ? sorted[n - 1] : sorted[top_k - 1];
     uint64_t total = 0;
     for (int32_t v = 0; v < V; ++v) {
-        e[v] = (z[v] >= t) ? oracle_exp_neg(z[v] - m) : 0.0f;
+        int allowed = v >= allow_lo && v < allow_hi;
+        e[v] = (allowed && z[v] >= t) ? oracle_exp_neg(z[v] - m) : 0.0f;
         total += oracle_weight_of(e[v]);
     }
     *Z = total;
     free(sorted);
     free(z);
+}
+
+void oracle_sampling_row(const float *logit_c, const float *logit_u, int32_t V, float cfg_scale,
+                         float temperature, int32_t top_k, float *e, uint64_t *Z) {
+    oracle_sampling_row_range(logit_c, logit_u, V, cfg_scale, temperature, top_k, 0, V, e, Z);
 }
 
 /* ----------------------------------------------------------------- decisions */

@@ -15,7 +15,9 @@
  *
  * Parity status of each part (what pins it, see tests/test_oracle_*.py):
  *   philox4x32-10 ............ published known-answer vectors
- *   EXP / sampling weights ... double-precision softmax, K = V, K = 1
+ *   EXP / sampling weights ... double-precision softmax, K = V, K = 1;
+ *                              forced-token ranges: the unmasked routine on
+ *                              the sliced row, a range of one id is one-hot
  *   integer inverse CDF ...... exhaustive enumeration on small normalisers
  *   accept + residual ........ Theorem 1 (appendix) by chi-square, closed-form
  *                              rejection rate, p = q never rejects
@@ -83,6 +85,12 @@ uint64_t oracle_weight_of(float e);
 void oracle_sampling_row(const float *logit_c, const float *logit_u, int32_t V, float cfg_scale,
                          float temperature, int32_t top_k, float *e, uint64_t *Z);
 
+/* The same with a forced-token mask: only ids in [allow_lo, allow_hi) (indices
+ * into the row, 0 <= allow_lo < allow_hi <= V) can have weight. */
+void oracle_sampling_row_range(const float *logit_c, const float *logit_u, int32_t V, float cfg_scale,
+                               float temperature, int32_t top_k, int32_t allow_lo, int32_t allow_hi, float *e,
+                               uint64_t *Z);
+
 /* ---- decisions on integer weights (probability = w / Z) */
 int32_t oracle_accept(uint32_t u32, uint64_t w_p, uint64_t Z_p, uint64_t w_q, uint64_t Z_q);
 int32_t oracle_keep(float tau, uint64_t w_p, uint64_t Z_p, uint64_t w_q, uint64_t Z_q);
@@ -107,6 +115,12 @@ void oracle_destroy(oracle_ctx *);
 int oracle_prefill(oracle_ctx *, int32_t n_seqs, const int32_t *const *cond_ids, const int32_t *cond_len,
                    const int32_t *const *uncond_ids, const int32_t *uncond_len,
                    const int32_t *n_image_tokens);
+/* Forced tokens: image position i of sequence `seq` may only take ids in
+ * [first_id[i], end_id[i]) (absolute ids inside the sampled range), i <
+ * n_positions; every other id has probability 0 there.  After oracle_prefill,
+ * which resets all positions to the whole sampled range. */
+int oracle_set_token_ranges(oracle_ctx *, int32_t seq, const int32_t *first_id, const int32_t *end_id,
+                            int32_t n_positions);
 int oracle_step(oracle_ctx *, oracle_step_result *out /* [n_seqs] */);
 /* Same decisions, but the logits come from the caller instead of the forward:
  * logits is [n_seqs][2 (cond, uncond)][L][V_s] fp32; the KV cache is not

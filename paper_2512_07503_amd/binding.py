@@ -84,7 +84,9 @@ def lib():
                                               C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                               C.c_int32, C.c_int32, C.POINTER(C.c_float)]
         L.sjd_op_sampling_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                                           C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+                                           C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
+        L.sjd_set_token_ranges.argtypes = [C.c_void_p, C.c_int32, IP, IP, C.c_int32]
         L.sjd_op_philox.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_int32]
         _lib = L
     return _lib
@@ -133,6 +135,7 @@ class Decoder:
         sp = Sampling(cfg_scale, temperature, top_k, reuse_tau, seed, init_mode, row_width)
         self.ctx = C.c_void_p()
         self.L, self.Vs, self.n_seqs = window, arch["sample_hi"] - arch["sample_lo"], 0
+        self.sparse_rows = True   # rows of the sampling distribution are stored as kept (id, weight) pairs
         # The context runs on the caller's current stream, unless that is the default stream: the library can only
         # capture its step into a HIP graph on an ordinary stream, so it then gets one of its own (default priority).
         # Either way the weights must be complete before sjd_create reads them.
@@ -192,6 +195,14 @@ class Decoder:
         out = np.zeros((self.n_seqs, 2, self.L, self.Vs), dtype=np.float32)
         _check(lib().sjd_debug_copy_logits(self.ctx, out.ctypes.data_as(C.POINTER(C.c_float))), self.ctx)
         return out
+
+    def set_token_ranges(self, seq, first_id, end_id):
+        """sjd_set_token_ranges: position i of sequence seq may only take ids in [first_id[i], end_id[i])."""
+        IP = C.POINTER(C.c_int32)
+        lo = np.ascontiguousarray(first_id, dtype=np.int32)
+        hi = np.ascontiguousarray(end_id, dtype=np.int32)
+        assert lo.shape == hi.shape and lo.ndim == 1
+        return lib().sjd_set_token_ranges(self.ctx, seq, lo.ctypes.data_as(IP), hi.ctypes.data_as(IP), len(lo))
 
     def tokens(self, seq=0):
         n = C.c_int32(0)
@@ -283,15 +294,23 @@ def op_window_attention(q, k, v, ctx, page_tokens=64, flags=0, repeat=1):
     return out, ms.value
 
 
-def op_sampling_rows(logits_c, logits_u, cfg_scale, temperature, top_k, repeat=1):
-    """float32 CUDA [rows,V] x2 -> (e float32 [rows,V], Z int64-viewed uint64 [rows], avg_ms)."""
+def op_sampling_rows(logits_c, logits_u, cfg_scale, temperature, top_k, repeat=1, allow_lo=None, allow_hi=None, kept=False):
+    """float32 CUDA [rows,V] x2 -> (e float32 [rows,V], Z int64-viewed uint64 [rows], avg_ms); with kept=True also the
+    stored form of the rows: (kept_ids int32 [rows,V], kept_cnt int32 [rows]).  allow_lo / allow_hi: int32 CUDA [rows]."""
     import torch
     rows, V = logits_c.shape
     e = torch.empty((rows, V), dtype=torch.float32, device=logits_c.device)
     Z = torch.zeros(rows, dtype=torch.int64, device=logits_c.device)
+    ids = torch.zeros((rows, V), dtype=torch.int32, device=logits_c.device) if kept else None
+    cnt = torch.zeros(rows, dtype=torch.int32, device=logits_c.device) if kept else None
     ms = C.c_float(0)
     _check(lib().sjd_op_sampling_rows(_stream_ptr(), logits_c.data_ptr(), logits_u.data_ptr(), e.data_ptr(), Z.data_ptr(),
-                                      rows, V, cfg_scale, temperature, top_k, repeat, C.byref(ms)))
+                                      rows, V, cfg_scale, temperature, top_k,
+                                      allow_lo.data_ptr() if allow_lo is not None else None,
+                                      allow_hi.data_ptr() if allow_hi is not None else None,
+                                      ids.data_ptr() if kept else None, cnt.data_ptr() if kept else None, repeat, C.byref(ms)))
+    if kept:
+        return e, Z, ms.value, ids, cnt
     return e, Z, ms.value
 
 

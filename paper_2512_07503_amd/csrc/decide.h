@@ -16,7 +16,7 @@ struct DecideState {
     int32_t *win_tok;  // [S][L]   window tokens (slot 0 unused)
     int32_t *anchor;   // [S][2]   first window input of the cond / uncond branch
     int32_t *ref_row;  // [S][L]   slot -> reference row of the previous step, -1 = uniform, -2 = one-hot at the draft,
-                       //          <= -3: row -3 - ref of hist_e
+                       //          <= -3: kept row -3 - ref (hist_*)
     int32_t *n_img;    // [S]      image tokens final so far
     int32_t *n_image;  // [S]      image tokens wanted
     int32_t *kv_len;   // [S][2]   committed cache positions per branch
@@ -26,10 +26,23 @@ struct DecideState {
     int32_t *cand;     // [S][L]   per output row: the token drawn (or kept) there this step
     int32_t *cand_new; // [S][L]   per slot of the NEXT window: the draw for a slot that never had a draft (init_mode 3)
     uint32_t *step;    // [1]      step counter (0 after prefill)
-    float *e_buf[2];   // [S][L][V] softmax weights, ping-pong by step parity
-    uint64_t *Z_buf[2];// [S][L]
-    float *hist_e;     // [S][row_width][V]  init_mode 4: the row under which image token i became final, at i % row_width
-    uint64_t *hist_Z;  // [S][row_width]
+    // Rows of the sampling distribution, stored as the kept (id, weight) pairs in ascending id order: top-K leaves a
+    // few thousand of V entries.  A row has room for `cap` = V pairs (ties at the K-th value, or K >= V, can keep a
+    // whole row); only the first cnt are ever written or read.  Ping-pong by step parity: this step's rows and the
+    // previous step's, which are the references of the window's drafts.
+    int32_t cap;
+    int32_t *ids_buf[2]; // [S][L][cap] ids relative to sample_lo
+    float *e_buf[2];     // [S][L][cap] softmax weights EXP(z - max z)
+    int32_t *cnt_buf[2]; // [S][L]
+    uint64_t *Z_buf[2];  // [S][L] integer normalisers
+    // init_mode 4: the row under which image token i became final, at i % row_width
+    int32_t *hist_ids;   // [S][row_width][cap]
+    float *hist_e;       // [S][row_width][cap]
+    int32_t *hist_cnt;   // [S][row_width]
+    uint64_t *hist_Z;    // [S][row_width]
+    // Forced-token masks: image position i of sequence s may only take ids in [allow_lo, allow_hi) (relative to
+    // sample_lo); every other id has probability 0 there.  [S][max_img]; the whole range by default.
+    int32_t *allow_lo, *allow_hi;
     sjd_step_result *res; // [S]
 };
 
@@ -65,6 +78,12 @@ hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingPar
 hipError_t launch_keep_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 
 // stand-alone forms for kernel tests
-hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,
-                                      int V, const SamplingParams &sp);
+// rows of [V] logits -> kept pairs ids / e [rows][V] (ascending ids), cnt [rows], Z [rows]; allow_lo / allow_hi [rows]
+// (may be NULL) restrict row r to ids in [allow_lo[r], allow_hi[r])
+hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, int32_t *ids, float *e, int32_t *cnt,
+                                      uint64_t *Z, int rows, int V, const SamplingParams &sp, const int32_t *allow_lo,
+                                      const int32_t *allow_hi);
+// e_dense [rows][V] (zero-filled by the caller) <- the kept pairs
+hipError_t launch_scatter_rows(hipStream_t st, const int32_t *ids, const float *e, const int32_t *cnt, float *e_dense, int rows,
+                               int V);
 hipError_t launch_philox_fill(hipStream_t st, uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n);

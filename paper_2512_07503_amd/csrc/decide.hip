@@ -142,51 +142,277 @@ SJD_D uint32_t block_max_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
 }
 
 // ------------------------------------------------------------------ a10: the sampling distribution
-// One block per row.  Radix select (4 passes of 8 bits over order keys) finds the K-th largest guided
-// logit exactly; the logits are re-read from L2 in every pass.
+// One workgroup of 1024 threads per position.  The guided logits of the row are read from memory once and stay in
+// registers as order keys (thread t holds ids t, t + 1024, ...); the row leaves the kernel as its kept (id, weight)
+// pairs in ascending id order plus the integer normaliser.
+//
+// The K-th largest key is found exactly by narrowing a range of candidates with LDS histograms:
+//   round 0   bins in d = max - z (fp32; monotone in z), 64 per octave of d: the bulk of a row lies far below its
+//             maximum and spreads over many bins, so the histogram's atomics rarely collide.  The bin that holds the
+//             K-th largest key and the number of keys above it follow from a prefix sum over the bins; the smallest
+//             and largest key of that bin bound the candidates;
+//   rounds 1+ 2048 equal bins over the remaining key range [lo, hi] until lo == hi (each round takes 11 bits off
+//             the range: at most three rounds).
+// Ties at the K-th value are all kept (they share a key), so nothing ever needs a tie-break.
 struct SampleRowsArgs {
     const float *lc_base, *lu_base;  // row r = (s, k): base + s * seq_stride + k * V
     long seq_stride;
     int L;                           // rows per sequence
-    float *e_base[2];                // + (s * L + k) * V; index = *step & 1 (0 when step == NULL)
-    uint64_t *Z_base[2];             // + s * L + k
+    int32_t *ids_base[2];            // + (s * L + k) * cap; index = *step & 1 (0 when step == NULL)
+    float *e_base[2];
+    int32_t *cnt_base[2];            // + s * L + k
+    uint64_t *Z_base[2];
+    long cap;
     const uint32_t *step;
     const int32_t *Le;               // [S] active rows per sequence, NULL = all
+    // allowed id range of a row (NULL = all ids): allow_lo / allow_hi index s * allow_stride + allow_first[s] + k
+    // (allow_first NULL: 0)
+    const int32_t *allow_lo, *allow_hi, *allow_first;
+    long allow_stride;
     int V, top_k;
     float cfg_scale, inv_t;
 };
 
-__global__ void sample_rows_kernel(SampleRowsArgs a) {
+constexpr int kSelBins = 2048;
+
+// First bin (ascending index) at which the running sum of hist reaches `want` (1 <= want <= total); `before` = the
+// sum of the bins below it.  2048 bins, 1024 threads (two bins each); result in all threads.
+SJD_D void find_bin(const uint32_t *hist, uint32_t want, uint32_t *wsum /* [16] */, uint32_t *out /* [2] */, uint32_t &bin,
+                    uint32_t &before) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t c0 = hist[2 * tid], c1 = hist[2 * tid + 1], mine = c0 + c1;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t excl = incl - mine;
+    for (int w = 0; w < wave; ++w) excl += wsum[w];
+    if (excl < want && want <= excl + mine) {   // exactly one thread
+        const bool first = want <= excl + c0;
+        out[0] = 2 * tid + (first ? 0 : 1);
+        out[1] = first ? excl : excl + c0;
+    }
+    __syncthreads();
+    bin = out[0];
+    before = out[1];
+    __syncthreads();   // out and wsum may be reused
+}
+
+SJD_D uint32_t block_min_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    for (int d = 32; d > 0; d >>= 1) {
+        uint32_t o = __shfl_down(v, d, 64);
+        v = o < v ? o : v;
+    }
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0xFFFFFFFFu;
+        for (int i = 0; i < nw; ++i) t = scratch[i] < t ? scratch[i] : t;
+        scratch[16] = t;
+    }
+    __syncthreads();
+    return scratch[16];
+}
+
+// bin of round 0: 64 bins per octave of d = max - z from 2^-12 up (everything nearer the maximum in bin 0,
+// everything from 2^20 on in the last bin); non-decreasing in d, hence non-increasing in z
+SJD_D int dist_bin(float m, uint32_t key) {
+    const float d = m - key_to_float(key);
+    const int b = (int)(__builtin_bit_cast(uint32_t, d) >> 17) - 115 * 64;
+    return b < 0 ? 0 : (b > kSelBins - 1 ? kSelBins - 1 : b);
+}
+
+template <int VPT>
+__global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs a) {
     const int r = blockIdx.x, s = r / a.L, k = r % a.L;
     if (a.Le && k >= a.Le[s]) return;
     const float *lc = a.lc_base + (long)s * a.seq_stride + (long)k * a.V;
     const float *lu = a.lu_base + (long)s * a.seq_stride + (long)k * a.V;
     const uint32_t par = a.step ? (*a.step & 1u) : 0u;
-    float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
-    const int V = a.V, tid = threadIdx.x, nt = blockDim.x;
-
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sel[2];
+    const long row = (long)s * a.L + k;
+    int32_t *ids = a.ids_base[par] + row * a.cap;
+    float *e = a.e_base[par] + row * a.cap;
+    const int V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int alo = 0, ahi = V;
+    if (a.allow_lo) {
+        const long j = (long)s * a.allow_stride + (a.allow_first ? a.allow_first[s] : 0) + k;
+        alo = a.allow_lo[j];
+        ahi = a.allow_hi[j];
+    }
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t wsum[16], sel[2];
     __shared__ uint32_t scratch32[17];
     __shared__ uint64_t scratch64[17];
 
+    uint32_t key[VPT];  // order key of the guided logit; 0 (below every real key) for ids that are not candidates
     uint32_t kmax = 0;
-    for (int v = tid; v < V; v += nt) {
-        uint32_t key = order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t));
-        kmax = key > kmax ? key : kmax;
+    // The loads are unconditional (index clamped to the row) and issued in batches: a load under `if (v < V)` is
+    // waited for inside its branch, and a thread would pay one memory round trip per element.
+    constexpr int kBatch = VPT < 16 ? VPT : 16;
+#pragma unroll
+    for (int i0 = 0; i0 < VPT; i0 += kBatch) {
+        float c[kBatch], u[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
+            c[j] = lc[vv];
+            u[j] = lu[vv];
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int i = i0 + j, v = tid + i * 1024;
+            const uint32_t kk = order_key(guided(c[j], u[j], a.cfg_scale, a.inv_t));
+            key[i] = v >= alo && v < ahi ? kk : 0u;
+            kmax = key[i] > kmax ? key[i] : kmax;
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one batch of loads in flight at a time: the keys need the registers
     }
     kmax = block_max_u32(kmax, scratch32);
     const float m = key_to_float(kmax);
 
-    uint32_t thresh = 0;  // keep everything
-    if (a.top_k < V) {
+    uint32_t thresh = 1u;   // every candidate
+    if (a.top_k < ahi - alo) {
+        // round 0: bins of the distance to the maximum
+        hist[2 * tid] = 0u;
+        hist[2 * tid + 1] = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            if (key[i]) atomicAdd(&hist[dist_bin(m, key[i])], 1u);
+        __syncthreads();
+        uint32_t bin, before;
+        find_bin(hist, (uint32_t)a.top_k, wsum, sel, bin, before);
+        uint32_t want = (uint32_t)a.top_k - before;   // rank of the K-th largest among the keys of that bin, from the top
+        uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            if (key[i] && dist_bin(m, key[i]) == (int)bin) {
+                lo = key[i] < lo ? key[i] : lo;
+                hi = key[i] > hi ? key[i] : hi;
+            }
+        lo = block_min_u32(lo, scratch32);
+        hi = block_max_u32(hi, scratch32);
+        // rounds 1+: equal bins over [lo, hi], counted from the top
+        for (int round = 0; round < 4 && lo != hi; ++round) {   // block-uniform; three rounds exhaust 32 bits
+            const uint32_t span = hi - lo;
+            const int width = 32 - __builtin_clz(span);          // bits of span
+            const int shift = width > 11 ? width - 11 : 0;       // (span >> shift) < 2048
+            hist[2 * tid] = 0u;
+            hist[2 * tid + 1] = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < VPT; ++i)
+                if (key[i] >= lo && key[i] <= hi) atomicAdd(&hist[kSelBins - 1 - ((key[i] - lo) >> shift)], 1u);
+            __syncthreads();
+            find_bin(hist, want, wsum, sel, bin, before);
+            want -= before;
+            const uint32_t nlo = lo + ((uint32_t)(kSelBins - 1 - bin) << shift);
+            uint32_t nhi = nlo + ((1u << shift) - 1u);
+            if (nhi < nlo || nhi > hi) nhi = hi;
+            lo = nlo;
+            hi = nhi;
+        }
+        thresh = lo;
+    }
+
+    // kept pairs in ascending id order: id = tid + 1024 i, so (i, wave, lane) ascending.  Every wavefront counts its
+    // kept ids per i; a prefix sum over the (i, wave) counts gives each wavefront's first output slot.
+    __shared__ uint32_t base[VPT * 16];
+    {
+        uint32_t count_i = 0;   // lane i of a wavefront ends up with the wavefront's count for index i (VPT <= 64)
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const uint32_t c = (uint32_t)__popcll(__ballot(key[i] >= thresh && key[i] != 0u));
+            count_i = lane == i ? c : count_i;
+        }
+        if (lane < VPT) base[lane * 16 + wave] = count_i;
+    }
+    __syncthreads();
+    {
+        const uint32_t mine = tid < VPT * 16 ? base[tid] : 0u;
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t excl = incl - mine;
+        for (int w = 0; w < wave; ++w) excl += wsum[w];
+        if (tid < VPT * 16) base[tid] = excl;
+        if (tid == VPT * 16 - 1) a.cnt_base[par][row] = (int32_t)(excl + mine);
+        __syncthreads();
+    }
+    // (the ballots are taken again rather than kept: VPT 64-bit masks would not fit the scalar registers; the empty
+    // asm keeps the compiler from carrying them over from the counting pass)
+    asm volatile("" : "+s"(thresh));
+    uint64_t zsum = 0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const bool keep = key[i] >= thresh && key[i] != 0u;
+        const uint64_t mask = __ballot(keep);
+        if (keep) {
+            const uint32_t pos = base[i * 16 + wave] + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            const float ev = exp_neg(key_to_float(key[i]) - m);
+            ids[pos] = tid + i * 1024;
+            e[pos] = ev;
+            zsum += weight_of(ev);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // one index at a time: nothing of the next ones is fetched ahead into registers
+    }
+    zsum = block_sum_u64(zsum, scratch64);
+    if (tid == 0) a.Z_base[par][row] = zsum;
+}
+
+// Rows wider than 64 * 1024 ids: the same result from a multi-pass radix select over keys that are recomputed from the
+// logits in every pass (one workgroup per row; kept pairs appended by one wavefront at a time in id order).
+__global__ __launch_bounds__(1024) void sample_rows_wide_kernel(SampleRowsArgs a) {
+    const int r = blockIdx.x, s = r / a.L, k = r % a.L;
+    if (a.Le && k >= a.Le[s]) return;
+    const float *lc = a.lc_base + (long)s * a.seq_stride + (long)k * a.V;
+    const float *lu = a.lu_base + (long)s * a.seq_stride + (long)k * a.V;
+    const uint32_t par = a.step ? (*a.step & 1u) : 0u;
+    const long row = (long)s * a.L + k;
+    int32_t *ids = a.ids_base[par] + row * a.cap;
+    float *e = a.e_base[par] + row * a.cap;
+    const int V = a.V, tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
+    int alo = 0, ahi = V;
+    if (a.allow_lo) {
+        const long j = (long)s * a.allow_stride + (a.allow_first ? a.allow_first[s] : 0) + k;
+        alo = a.allow_lo[j];
+        ahi = a.allow_hi[j];
+    }
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sel[2];
+    __shared__ uint32_t scratch32[17];
+    __shared__ uint64_t scratch64[17];
+    __shared__ uint32_t wcnt[16];
+    auto key_of = [&](int v) { return order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t)); };
+
+    uint32_t kmax = 0;
+    for (int v = alo + tid; v < ahi; v += nt) {
+        const uint32_t kk = key_of(v);
+        kmax = kk > kmax ? kk : kmax;
+    }
+    kmax = block_max_u32(kmax, scratch32);
+    const float m = key_to_float(kmax);
+
+    uint32_t thresh = 1u;
+    if (a.top_k < ahi - alo) {
         uint32_t prefix = 0, mask = 0, want = (uint32_t)a.top_k;
         for (int shift = 24; shift >= 0; shift -= 8) {
             for (int i = tid; i < 256; i += nt) hist[i] = 0;
             __syncthreads();
-            for (int v = tid; v < V; v += nt) {
-                uint32_t key = order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t));
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            for (int v = alo + tid; v < ahi; v += nt) {
+                const uint32_t kk = key_of(v);
+                if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1u);
             }
             __syncthreads();
             if (tid == 0) {
@@ -207,169 +433,50 @@ __global__ void sample_rows_kernel(SampleRowsArgs a) {
         }
         thresh = prefix;
     }
-
     uint64_t zsum = 0;
-    for (int v = tid; v < V; v += nt) {
-        float z = guided(lc[v], lu[v], a.cfg_scale, a.inv_t);
-        float ev = order_key(z) >= thresh ? exp_neg(z - m) : 0.0f;
-        e[v] = ev;
-        zsum += weight_of(ev);
-    }
-    zsum = block_sum_u64(zsum, scratch64);
-    if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
-}
-
-// Register-resident form for V <= 1024 * VPT: the guided logits of a row are read from HBM once and stay in
-// registers (thread t holds elements t, t + 1024, ...).  The K-th largest key is found one bit at a time, most
-// significant first: count the candidates whose next bit is 1; if at least `want` of them exist the K-th
-// largest has that bit set, otherwise it does not and `want` drops by that count.  32 counting rounds of
-// wavefront ballots and one LDS exchange each, exact; after the first 10 bits the rounds run over the compacted
-// list of keys that still compete (see below).
-// adds one wave-uniform count per wavefront over a block of 16 wavefronts; scratch (16-byte aligned) alternates
-// between rounds.  The 16 counts come back as four 16-byte LDS reads: a round of the select is this exchange and
-// little else, and a loop of 16 dependent single reads made it twice as long.
-SJD_D uint32_t block_sum_wave_counts(uint32_t wave_count, uint32_t *scratch /* [16] */) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) scratch[wave] = wave_count;
-    __syncthreads();
-    const uint4 *q = reinterpret_cast<const uint4 *>(scratch);
-    const uint4 a = q[0], b = q[1], c = q[2], d = q[3];
-    return ((a.x + a.y) + (a.z + a.w)) + ((b.x + b.y) + (b.z + b.w)) + ((c.x + c.y) + (c.z + c.w)) + ((d.x + d.y) + (d.z + d.w));
-}
-
-// Wall-clock stamps of block 0 for probes (compiled out of the library)
-#ifdef SJD_PHASE_TIMING
-__device__ unsigned long long g_sample_phase[8];
-#define SJD_SAMPLE_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_sample_phase[i] = wall_clock64(); } while (0)
-#else
-#define SJD_SAMPLE_STAMP(i) do { } while (0)
-#endif
-
-template <int VPT>
-__global__ __launch_bounds__(1024) void sample_rows_reg_kernel(SampleRowsArgs a) {
-    const int r = blockIdx.x, s = r / a.L, k = r % a.L;
-    if (a.Le && k >= a.Le[s]) return;
-    const float *lc = a.lc_base + (long)s * a.seq_stride + (long)k * a.V;
-    const float *lu = a.lu_base + (long)s * a.seq_stride + (long)k * a.V;
-    const uint32_t par = a.step ? (*a.step & 1u) : 0u;
-    float *e = a.e_base[par] + ((long)s * a.L + k) * a.V;
-    const int V = a.V, tid = threadIdx.x;
-    __shared__ __align__(16) uint32_t cnt[2][16];
-    __shared__ __align__(16) uint32_t cnt2[16];
-    __shared__ uint32_t scratch32[17];
-    __shared__ uint64_t scratch64[17];
-
-    SJD_SAMPLE_STAMP(0);
-    uint32_t key[VPT];  // order key of the guided logit; 0 (below every real key) past the end of the row
-    uint32_t kmax = 0;
-    // The loads are unconditional (index clamped to the row) and issued in batches: a load under `if (v < V)` is
-    // waited for inside its branch, and a thread would pay one memory round trip per element.
-    constexpr int kBatch = VPT < 16 ? VPT : 16;
-#pragma unroll
-    for (int i0 = 0; i0 < VPT; i0 += kBatch) {
-        float c[kBatch], u[kBatch];
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
-            c[j] = lc[vv];
-            u[j] = lu[vv];
+    uint32_t n_out = 0;   // block-uniform
+    for (int v0 = alo; v0 < ahi; v0 += nt) {
+        const int v = v0 + tid;
+        const uint32_t kk = v < ahi ? key_of(v) : 0u;
+        const bool keep = v < ahi && kk >= thresh;
+        const uint64_t mk = __ballot(keep);
+        if (lane == 0) wcnt[wave] = (uint32_t)__popcll(mk);
+        __syncthreads();
+        uint32_t pos = n_out, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) pos += wcnt[w];
+            total += wcnt[w];
         }
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const int i = i0 + j, v = tid + i * 1024;
-            const uint32_t kk = order_key(guided(c[j], u[j], a.cfg_scale, a.inv_t));
-            key[i] = v < V ? kk : 0u;
-            kmax = key[i] > kmax ? key[i] : kmax;
-        }
-    }
-    kmax = block_max_u32(kmax, scratch32);
-    const float m = key_to_float(kmax);
-    SJD_SAMPLE_STAMP(1);
-
-    uint32_t thresh = 0;
-    if (a.top_k < V) {
-        uint32_t prefix = 0, want = (uint32_t)a.top_k;
-        // one counting round over the keys in registers
-        auto round_all = [&](int bit) {
-            const uint32_t hi_mask = bit == 31 ? 0u : ~((2u << bit) - 1u);  // bits above `bit`
-            const uint32_t probe = prefix | (1u << bit);
-            uint32_t c = 0;  // wave-uniform: ballots, not shuffles
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) c += (uint32_t)__popcll(__ballot((key[i] & (hi_mask | (1u << bit))) == probe));
-            c = block_sum_wave_counts(c, cnt[bit & 1]);
-            if (c >= want) prefix = probe; else want -= c;
-        };
-        // The top kSplitBits bits (sign, exponent, first mantissa bit) over all keys.  What still competes for the
-        // K-th place afterwards are the keys that share those bits with it: usually a few percent of the row.  If
-        // they fit the LDS list they are compacted (any order: the rounds only count) and the remaining rounds run
-        // over at most kCandPerThread keys per thread instead of VPT; otherwise the rounds go on over all keys.
-        constexpr int kSplitBits = 10, kCandPerThread = 4, kCandMax = 1024 * kCandPerThread;
-        for (int bit = 31; bit > 31 - kSplitBits; --bit) round_all(bit);
-        SJD_SAMPLE_STAMP(2);
-        constexpr uint32_t top_mask = ~((1u << (32 - kSplitBits)) - 1u);
-        __shared__ uint32_t cand[kCandMax];
-        __shared__ uint32_t n_cand_lds;
-        uint32_t n_cand = 0;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) n_cand += (uint32_t)__popcll(__ballot((key[i] & top_mask) == prefix));
-        n_cand = block_sum_wave_counts(n_cand, cnt2);
-        if (n_cand <= (uint32_t)kCandMax) {
-            if (tid == 0) n_cand_lds = 0u;
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                if ((key[i] & top_mask) == prefix) cand[atomicAdd(&n_cand_lds, 1u)] = key[i];
-            __syncthreads();
-            SJD_SAMPLE_STAMP(3);
-            uint32_t ck[kCandPerThread];
-            bool cv[kCandPerThread];
-#pragma unroll
-            for (int j = 0; j < kCandPerThread; ++j) {
-                cv[j] = (uint32_t)(tid + 1024 * j) < n_cand;
-                ck[j] = cv[j] ? cand[tid + 1024 * j] : 0u;
-            }
-            for (int bit = 31 - kSplitBits; bit >= 0; --bit) {
-                const uint32_t hi_mask = ~((2u << bit) - 1u);
-                const uint32_t probe = prefix | (1u << bit);
-                uint32_t c = 0;
-#pragma unroll
-                for (int j = 0; j < kCandPerThread; ++j)
-                    c += (uint32_t)__popcll(__ballot(cv[j] && (ck[j] & (hi_mask | (1u << bit))) == probe));
-                c = block_sum_wave_counts(c, cnt[bit & 1]);
-                if (c >= want) prefix = probe; else want -= c;
-            }
-        } else {
-            for (int bit = 31 - kSplitBits; bit >= 0; --bit) round_all(bit);
-        }
-        thresh = prefix;
-    }
-    SJD_SAMPLE_STAMP(4);
-
-    uint64_t zsum = 0;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-        const int v = tid + i * 1024;
-        if (v < V) {
-            const float z = key_to_float(key[i]);
-            const float ev = key[i] >= thresh ? exp_neg(z - m) : 0.0f;
-            e[v] = ev;
+        if (keep) {
+            pos += (uint32_t)__popcll(mk & ((1ull << lane) - 1ull));
+            const float ev = exp_neg(key_to_float(kk) - m);
+            ids[pos] = v;
+            e[pos] = ev;
             zsum += weight_of(ev);
         }
+        n_out += total;
+        __syncthreads();
     }
-    SJD_SAMPLE_STAMP(5);
     zsum = block_sum_u64(zsum, scratch64);
-    if (tid == 0) a.Z_base[par][(long)s * a.L + k] = zsum;
-    SJD_SAMPLE_STAMP(6);
+    if (tid == 0) {
+        a.Z_base[par][row] = zsum;
+        a.cnt_base[par][row] = (int32_t)n_out;
+    }
 }
 
 hipError_t launch_sample_rows_any(hipStream_t st, const SampleRowsArgs &a, int rows) {
     const int V = a.V;
-    if (V <= 1024 * 4) sample_rows_reg_kernel<4><<<rows, 1024, 0, st>>>(a);
-    else if (V <= 1024 * 16) sample_rows_reg_kernel<16><<<rows, 1024, 0, st>>>(a);
-    else if (V <= 1024 * 32) sample_rows_reg_kernel<32><<<rows, 1024, 0, st>>>(a);
-    else if (V <= 1024 * 64) sample_rows_reg_kernel<64><<<rows, 1024, 0, st>>>(a);
-    else sample_rows_kernel<<<rows, 1024, 0, st>>>(a);
+    if (V <= 1024 * 4) sample_rows_sparse_kernel<4><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 16) sample_rows_sparse_kernel<16><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 32) sample_rows_sparse_kernel<32><<<rows, 1024, 0, st>>>(a);
+    else if (V <= 1024 * 64) sample_rows_sparse_kernel<64><<<rows, 1024, 0, st>>>(a);
+    else sample_rows_wide_kernel<<<rows, 1024, 0, st>>>(a);
     return hipGetLastError();
+}
+
+__global__ void scatter_rows_kernel(const int32_t *ids, const float *e, const int32_t *cnt, float *e_dense, int V) {
+    const int r = blockIdx.x, n = cnt[r];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) e_dense[(long)r * V + ids[(long)r * V + i]] = e[(long)r * V + i];
 }
 
 // --------------------------------------------------------------------------------- window set-up
@@ -391,6 +498,10 @@ __global__ void init_window_kernel(DecideState d, uint64_t seed, int n_seqs, con
             d.kv_len[s * 2 + b] = prompt_len[s * 2 + b] - 1;
             d.anchor[s * 2 + b] = prompt_last[s * 2 + b];
         }
+    }
+    for (int i = threadIdx.x; i < d.max_img; i += blockDim.x) {   // no forced tokens until the caller sets some
+        d.allow_lo[(long)s * d.max_img + i] = 0;
+        d.allow_hi[(long)s * d.max_img + i] = d.V;
     }
     for (int k = threadIdx.x; k < d.L; k += blockDim.x) {
         int tok = 0;
@@ -434,31 +545,65 @@ __global__ void stage_prompt_kernel(RowMap rm, const int32_t *prompt, const int3
 
 constexpr int kRefUniform = -1, kRefOneHot = -2, kRefHist0 = -3;  // values of ref_row below 0 (<= -3: kept row -3 - ref)
 
-// Row and normaliser a reference code points at (nullptr: uniform or one-hot, which have no row)
-SJD_D const float *ref_row_ptr(const DecideState &d, int s, int rr, const float *e_ref, const uint64_t *Z_ref, int row_width,
-                               uint64_t &Z) {
-    if (rr >= 0) { Z = Z_ref[rr]; return e_ref + (long)rr * d.V; }
-    if (rr <= kRefHist0) {
-        const int h = kRefHist0 - rr;
-        Z = d.hist_Z[s * row_width + h];
-        return d.hist_e + ((long)s * row_width + h) * d.V;
+// A stored row: kept ids (ascending) with their weights, or one of the two distributions that have no row.
+struct RowRef {
+    const int32_t *ids;
+    const float *e;
+    int n;          // kept pairs
+    uint64_t Z;
+    int kind;       // 0 = stored row, kRefUniform, kRefOneHot
+};
+
+// weight of id x in a stored row (0 if it was not kept)
+SJD_D uint64_t row_weight(const RowRef &r, int x) {
+    int lo = 0, hi = r.n;   // first index whose id is >= x
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (r.ids[mid] < x) lo = mid + 1; else hi = mid;
     }
-    Z = rr == kRefOneHot ? 1ull : (uint64_t)d.V;
-    return nullptr;
+    return lo < r.n && r.ids[lo] == x ? weight_of(r.e[lo]) : 0ull;
 }
+
+SJD_D RowRef step_row(const DecideState &d, uint32_t par, int s, int k) {
+    const long row = (long)s * d.L + k;
+    RowRef r;
+    r.ids = d.ids_buf[par] + row * d.cap;
+    r.e = d.e_buf[par] + row * d.cap;
+    r.n = d.cnt_buf[par][row];
+    r.Z = d.Z_buf[par][row];
+    r.kind = 0;
+    return r;
+}
+
+// The distribution a reference code points at: a row of the previous step, a kept row, uniform or one-hot
+SJD_D RowRef ref_row_of(const DecideState &d, uint32_t par_ref, int s, int rr, int row_width) {
+    if (rr >= 0) return step_row(d, par_ref, s, rr);
+    RowRef r;
+    if (rr <= kRefHist0) {
+        const long h = (long)s * row_width + (kRefHist0 - rr);
+        r.ids = d.hist_ids + h * d.cap;
+        r.e = d.hist_e + h * d.cap;
+        r.n = d.hist_cnt[h];
+        r.Z = d.hist_Z[h];
+        r.kind = 0;
+        return r;
+    }
+    r.ids = nullptr; r.e = nullptr; r.n = 0;
+    r.Z = rr == kRefOneHot ? 1ull : (uint64_t)d.V;
+    r.kind = rr;
+    return r;
+}
+// weight of the draft x itself under its reference (a one-hot reference sits at that very token)
+SJD_D uint64_t ref_weight_of_draft(const RowRef &q, int x) { return q.kind == 0 ? row_weight(q, x) : 1ull; }
 
 // ------------------------------------------------------------------- a11: verification (Eq. 2)
 // One block per sequence; every draft is tested in parallel, the first rejection is found with a
 // wavefront ballot per 64 drafts and a minimum across wavefronts.
 __global__ void verify_kernel(DecideState d, uint64_t seed, int row_width) {
-    const int s = blockIdx.x, L = d.L, V = d.V;
+    const int s = blockIdx.x, L = d.L;
     const int Le = d.Le[s];
     if (Le == 0) return;
-    const uint32_t step = *d.step;
-    const float *e_new = d.e_buf[step & 1u] + (long)s * L * V;
-    const float *e_ref = d.e_buf[(step & 1u) ^ 1u] + (long)s * L * V;
-    const uint64_t *Z_new = d.Z_buf[step & 1u] + s * L;
-    const uint64_t *Z_ref = d.Z_buf[(step & 1u) ^ 1u] + s * L;
+    const uint32_t step = *d.step, par = step & 1u;
     __shared__ int first_reject;
     if (threadIdx.x == 0) first_reject = Le;
     __syncthreads();
@@ -469,12 +614,9 @@ __global__ void verify_kernel(DecideState d, uint64_t seed, int row_width) {
             uint32_t w[4];
             draw_words(seed, step, (uint32_t)(k - 1), (uint32_t)s, w);
             const int x = d.win_tok[s * L + k] - d.lo;
-            const uint64_t wp = weight_of(e_new[(long)(k - 1) * V + x]);
-            const int rr = d.ref_row[s * L + k];  // -1 uniform: 1 / V;  -2 one-hot at this very token: 1 / 1
-            uint64_t Zq;
-            const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
-            const uint64_t wq = qrow ? weight_of(qrow[x]) : 1ull;
-            rejected = !accept_rule(w[0], wp, Z_new[k - 1], wq, Zq);
+            const RowRef p = step_row(d, par, s, k - 1);
+            const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k], row_width);
+            rejected = !accept_rule(w[0], row_weight(p, x), p.Z, ref_weight_of_draft(q, x), q.Z);
         }
         const uint64_t mask = __ballot(rejected);
         if ((threadIdx.x & 63) == 0 && mask != 0ull) atomicMin(&first_reject, base + (threadIdx.x & ~63) + __builtin_ctzll(mask));
@@ -484,11 +626,6 @@ __global__ void verify_kernel(DecideState d, uint64_t seed, int row_width) {
 }
 
 // ---------------------------------------------------- a12 / a13: the draws of a step (Eq. 3, Eq. 5)
-// Block-wide inverse CDF over integer weights weight(v), v in [0, V): returns the first v whose inclusive
-// prefix sum exceeds floor(u64 * total / 2^64), or -1 when total == 0.  Two levels: (1) each wavefront sums a
-// contiguous segment with coalesced reads, every thread scans the <= 16 segment totals and knows which segment
-// holds the target; (2) the whole block re-reads that segment, a few consecutive ids per thread, one
-// block-wide scan of the per-thread sums names the thread, which walks its ids.  Integer sums: exact.
 SJD_D uint64_t shfl_up_u64(uint64_t v, int delta) {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
     lo = __shfl_up(lo, delta, 64);
@@ -496,66 +633,18 @@ SJD_D uint64_t shfl_up_u64(uint64_t v, int delta) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// support(v): a cheap test that is true wherever weight(v) != 0 (may be true elsewhere).  With top-K most weights of
-// a row are 0 and the costly ones (the residual takes two double-precision divisions per id) are only evaluated
-// where the test holds: a thread marks its ids in a bit mask first, with unconditional batched loads, then walks
-// the marked ones - a few per thread instead of all.  The sums are integer sums, so nothing changes in the result.
-struct AnySupport { SJD_D bool operator()(int) const { return true; } };
-template <typename F, typename S = AnySupport>
-SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20] shared */, S support = S()) {
+// Block-wide inverse CDF over the integer weights weight(i) of the n kept pairs of a row (ascending id, so the
+// prefix sums run in ascending token order; ids that were not kept have weight 0 and cannot be hit): returns the
+// first i whose inclusive prefix sum exceeds floor(u64 * total / 2^64), or -1 when total == 0.  Thread t owns the
+// consecutive pairs [t * per, t * per + per); a block-wide scan of the per-thread sums names the thread that holds
+// the target, which walks its pairs.  Integer sums: exact in any order.
+template <typename F>
+SJD_D int block_inverse_cdf(F weight, int n, uint64_t u64, uint64_t *sums /* [20] shared */) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6, nt = blockDim.x;
-    // level 1: wavefront w owns the contiguous segment [w * seg, (w + 1) * seg), read 64 consecutive ids at a time
-    const int per = (V + nt - 1) / nt;          // ids per thread at level 2
-    const int seg = per * 64;
-    const int v0 = wave * seg, v1 = v0 + seg < V ? v0 + seg : V;
-    uint64_t local = 0;
-    if (!std::is_same<S, AnySupport>::value && per <= 64) {
-        uint64_t marked = 0;
-#pragma unroll 8
-        for (int i = 0; i < per; ++i) {
-            const int v = v0 + lane + 64 * i;
-            const bool sup = support(v < V ? v : V - 1);   // the load inside is unconditional
-            if (v < v1 && sup) marked |= 1ull << i;
-        }
-        while (marked) {
-            const int i = __builtin_ctzll(marked);
-            marked &= marked - 1ull;
-            local += weight(v0 + lane + 64 * i);
-        }
-    } else {
-        // batches of 8 ids with clamped, unconditional loads (a loop of load - add pays a memory round trip per id)
-        for (int i0 = 0; i0 < per; i0 += 8) {
-            uint64_t wv[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int v = v0 + lane + 64 * (i0 + j);
-                wv[j] = weight(v < V ? v : V - 1);
-                if (v >= v1) wv[j] = 0;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) local += wv[j];
-        }
-    }
-    for (int d = 32; d > 0; d >>= 1) local += shfl_down_u64(local, d);
-    __syncthreads();
-    if (lane == 0) sums[wave] = local;
-    __syncthreads();
-    uint64_t total = 0;
-    for (int i = 0; i < nw; ++i) total += sums[i];
-    if (total == 0) return -1;
-    const uint64_t target = mulhi64(u64, total);
-    int hit_seg = 0;
-    uint64_t before = 0;
-    for (int i = 0; i < nw; ++i) {           // the segment whose range of prefix sums holds the target
-        if (before + sums[i] > target) { hit_seg = i; break; }
-        before += sums[i];
-    }
-    // level 2: the whole block re-reads that segment, thread t owning the `chunk` consecutive ids from s0 + t * chunk
-    const int s0 = hit_seg * seg, s1 = s0 + seg < V ? s0 + seg : V;
-    const int chunk = (seg + nt - 1) / nt;
-    const int c0 = s0 + tid * chunk, c1 = c0 + chunk < s1 ? c0 + chunk : s1;
+    const int per = (n + nt - 1) / nt;
+    const int c0 = tid * per < n ? tid * per : n, c1 = c0 + per < n ? c0 + per : n;
     uint64_t mine = 0;
-    for (int v = c0; v < c1; ++v) mine += weight(v);
+    for (int i = c0; i < c1; ++i) mine += weight(i);
     uint64_t incl = mine;
     for (int d = 1; d < 64; d <<= 1) {
         const uint64_t o = shfl_up_u64(incl, d);
@@ -564,17 +653,29 @@ SJD_D int block_inverse_cdf(F weight, int V, uint64_t u64, uint64_t *sums /* [20
     __syncthreads();
     if (lane == 63) sums[wave] = incl;
     __syncthreads();
-    uint64_t excl = before + incl - mine;
-    for (int i = 0; i < wave; ++i) excl += sums[i];
+    uint64_t total = 0, excl = incl - mine;
+    for (int i = 0; i < nw; ++i) {
+        if (i < wave) excl += sums[i];
+        total += sums[i];
+    }
+    if (total == 0) return -1;
+    const uint64_t target = mulhi64(u64, total);
     if (excl <= target && target < excl + mine) {   // exactly one thread
         uint64_t run = excl;
-        for (int v = c0; v < c1; ++v) {
-            run += weight(v);
-            if (run > target) { sums[18] = (uint64_t)v; break; }
+        for (int i = c0; i < c1; ++i) {
+            run += weight(i);
+            if (run > target) { sums[18] = (uint64_t)i; break; }
         }
     }
     __syncthreads();
     return (int)(int64_t)sums[18];
+}
+
+// token drawn from a stored row (id relative to sample_lo)
+SJD_D int draw_from_row(const RowRef &p, uint64_t u64, uint64_t *sums) {
+    auto w = [&](int i) { return weight_of(p.e[i]); };
+    const int i = block_inverse_cdf(w, p.n, u64, sums);
+    return p.ids[i < 0 ? 0 : i];
 }
 
 // One block per output row k of every sequence.  With a accepted drafts:
@@ -603,7 +704,7 @@ SJD_D int above_source(int k2, int n_img, int a, int Le, int row_width, int *src
 }
 
 __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_per_seq, int init_mode, int row_width) {
-    const int r = blockIdx.x, L = d.L, V = d.V, s = r / rows_per_seq;
+    const int r = blockIdx.x, L = d.L, s = r / rows_per_seq;
     int k = r % rows_per_seq;
     const int Le = d.Le[s];
     if (Le == 0) return;
@@ -618,11 +719,7 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
     } else if (k < a) {
         return;
     }
-    const uint32_t step = *d.step;
-    const float *e_new = d.e_buf[step & 1u] + (long)s * L * V;
-    const float *e_ref = d.e_buf[(step & 1u) ^ 1u] + (long)s * L * V;
-    const uint64_t *Z_new = d.Z_buf[step & 1u] + s * L;
-    const uint64_t *Z_ref = d.Z_buf[(step & 1u) ^ 1u] + s * L;
+    const uint32_t step = *d.step, par = step & 1u;
     extern __shared__ uint64_t sums[];
 
     uint32_t w[4];
@@ -630,53 +727,41 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
     const uint64_t u64 = ((uint64_t)w[1] << 32) | w[2];
     if (new_slot >= 0) {
         // init_mode 3: the last row of this step; init_mode 4: the distribution of the token one image row above
-        const float *src = e_new + (long)(Le - 1) * V;
-        uint64_t Zs = Z_new[Le - 1];
+        RowRef src = step_row(d, par, s, Le - 1);
         if (init_mode == 4) {
             int src_new;
             const int code = above_source(new_slot, d.n_img[s], a, Le, row_width, &src_new);
             if (code == kRefUniform) return;   // a uniform draft: the window update makes it
-            if (src_new >= 0) { src = e_new + (long)src_new * V; Zs = Z_new[src_new]; }
-            else if (code >= 0) { src = e_new + (long)code * V; Zs = Z_new[code]; }
-            else src = ref_row_ptr(d, s, code, e_ref, Z_ref, row_width, Zs);
+            if (src_new >= 0) src = step_row(d, par, s, src_new);
+            else if (code >= 0) src = step_row(d, par, s, code);
+            else src = ref_row_of(d, par ^ 1u, s, code, row_width);
         }
-        auto from_src = [&](int v) { return weight_of(src[v]); };
-        const int t = block_inverse_cdf(from_src, V, u64, sums);
+        const int t = draw_from_row(src, u64, sums);
         if (threadIdx.x == 0) d.cand_new[s * L + new_slot] = d.lo + t;
         return;
     }
-    const float *pk = e_new + (long)k * V;
-    const uint64_t Zp = Z_new[k];
-    auto from_p = [&](int v) { return weight_of(pk[v]); };
+    const RowRef p = step_row(d, par, s, k);
 
     int tok;
     if (k == a && a < Le - 1) {
-        const int rr = d.ref_row[s * L + a + 1];
-        uint64_t Zq;
-        const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
+        const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + a + 1], row_width);
         const int x = d.win_tok[s * L + a + 1] - d.lo;
-        auto resid = [&](int v) {
-            double P = prob(weight_of(pk[v]), Zp);
-            double Q = rr == kRefOneHot ? (v == x ? 1.0 : 0.0) : prob(qrow ? weight_of(qrow[v]) : 1ull, Zq);
+        // max(0, p - q) is 0 wherever p is: the pairs of p are all there is to sum over
+        auto resid = [&](int i) {
+            const int v = p.ids[i];
+            const double P = prob(weight_of(p.e[i]), p.Z);
+            const double Q = q.kind == kRefOneHot ? (v == x ? 1.0 : 0.0) : prob(q.kind == 0 ? row_weight(q, v) : 1ull, q.Z);
             return residual_weight(P, Q);
         };
-        // p(v) has weight 0 below 2^-40 (weight_of), and where p is 0 so is max(0, p - q)
-        auto p_support = [&](int v) { return pk[v] >= 0x1p-40f; };
-        tok = block_inverse_cdf(resid, V, u64, sums, p_support);
-        if (tok < 0) tok = block_inverse_cdf(from_p, V, u64, sums);
+        const int i = block_inverse_cdf(resid, p.n, u64, sums);
+        tok = i >= 0 ? p.ids[i] : draw_from_row(p, u64, sums);
     } else if (k > a && k <= Le - 2) {
         const int x = d.win_tok[s * L + k + 1] - d.lo;
-        const int rr = d.ref_row[s * L + k + 1];
-        uint64_t Zq;
-        const float *qrow = ref_row_ptr(d, s, rr, e_ref, Z_ref, row_width, Zq);
-        const uint64_t wq = qrow ? weight_of(qrow[x]) : 1ull;
-        if (keep_rule(tau, weight_of(pk[x]), Zp, wq, Zq)) {
-            tok = x;
-        } else {
-            tok = block_inverse_cdf(from_p, V, u64, sums);
-        }
+        const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k + 1], row_width);
+        if (keep_rule(tau, row_weight(p, x), p.Z, ref_weight_of_draft(q, x), q.Z)) tok = x;
+        else tok = draw_from_row(p, u64, sums);
     } else {
-        tok = block_inverse_cdf(from_p, V, u64, sums);
+        tok = draw_from_row(p, u64, sums);
     }
     if (threadIdx.x == 0) d.cand[s * L + k] = d.lo + tok;
 }
@@ -768,16 +853,20 @@ __global__ void commit_kernel(DecideState d, uint64_t seed, int init_mode, int r
 // init_mode 4: image token n_img + i became final under row i of this step (i <= a).  One block per (sequence, i);
 // where several of them share a slot of the ring (row_width <= a) the last one is the one kept.
 __global__ void keep_rows_kernel(DecideState d, int row_width) {
-    const int L = d.L, V = d.V, s = blockIdx.x / L, i = blockIdx.x % L;
+    const int L = d.L, s = blockIdx.x / L, i = blockIdx.x % L;
     if (d.Le[s] == 0) return;
     const int a = d.acc_len[s];
     if (i > a || i + row_width <= a) return;
-    const uint32_t step = *d.step;
-    const float *src = d.e_buf[step & 1u] + ((long)s * L + i) * V;
-    const int h = (d.n_img[s] + i) % row_width;
-    float *dst = d.hist_e + ((long)s * row_width + h) * V;
-    for (int v = threadIdx.x; v < V; v += blockDim.x) dst[v] = src[v];
-    if (threadIdx.x == 0) d.hist_Z[s * row_width + h] = d.Z_buf[step & 1u][s * L + i];
+    const RowRef src = step_row(d, *d.step & 1u, s, i);
+    const long h = (long)s * row_width + (d.n_img[s] + i) % row_width;
+    for (int j = threadIdx.x; j < src.n; j += blockDim.x) {
+        d.hist_ids[h * d.cap + j] = src.ids[j];
+        d.hist_e[h * d.cap + j] = src.e[j];
+    }
+    if (threadIdx.x == 0) {
+        d.hist_cnt[h] = src.n;
+        d.hist_Z[h] = src.Z;
+    }
 }
 
 __global__ void philox_fill_kernel(uint64_t seed, uint32_t row, uint32_t seq, uint32_t *out, int n) {
@@ -817,10 +906,16 @@ hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const Sampli
     a.lu_base = logits + (long)d.L * d.V;
     a.seq_stride = 2l * d.L * d.V;
     a.L = d.L;
-    a.e_base[0] = d.e_buf[0]; a.e_base[1] = d.e_buf[1];
-    a.Z_base[0] = d.Z_buf[0]; a.Z_base[1] = d.Z_buf[1];
+    for (int b = 0; b < 2; ++b) {
+        a.ids_base[b] = d.ids_buf[b]; a.e_base[b] = d.e_buf[b]; a.cnt_base[b] = d.cnt_buf[b]; a.Z_base[b] = d.Z_buf[b];
+    }
+    a.cap = d.cap;
     a.step = d.step;
     a.Le = d.Le;
+    a.allow_lo = d.allow_lo;
+    a.allow_hi = d.allow_hi;
+    a.allow_first = d.n_img;      // row k of sequence s predicts image position n_img[s] + k
+    a.allow_stride = d.max_img;
     a.V = d.V;
     a.top_k = sp.top_k;
     a.cfg_scale = sp.cfg_scale;
@@ -828,22 +923,36 @@ hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const Sampli
     return launch_sample_rows_any(st, a, n_seqs * d.L);
 }
 
-hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, float *e, uint64_t *Z, int rows,
-                                      int V, const SamplingParams &sp) {
+hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const float *lu, int32_t *ids, float *e, int32_t *cnt,
+                                      uint64_t *Z, int rows, int V, const SamplingParams &sp, const int32_t *allow_lo,
+                                      const int32_t *allow_hi) {
     SampleRowsArgs a;
     a.lc_base = lc;
     a.lu_base = lu;
     a.seq_stride = 0;
     a.L = rows;
+    a.ids_base[0] = a.ids_base[1] = ids;
     a.e_base[0] = a.e_base[1] = e;
+    a.cnt_base[0] = a.cnt_base[1] = cnt;
     a.Z_base[0] = a.Z_base[1] = Z;
+    a.cap = V;
     a.step = nullptr;
     a.Le = nullptr;
+    a.allow_lo = allow_lo;
+    a.allow_hi = allow_hi;
+    a.allow_first = nullptr;
+    a.allow_stride = 0;
     a.V = V;
     a.top_k = sp.top_k;
     a.cfg_scale = sp.cfg_scale;
     a.inv_t = sp.inv_temperature;
     return launch_sample_rows_any(st, a, rows);
+}
+
+hipError_t launch_scatter_rows(hipStream_t st, const int32_t *ids, const float *e, const int32_t *cnt, float *e_dense, int rows,
+                               int V) {
+    scatter_rows_kernel<<<rows, 256, 0, st>>>(ids, e, cnt, e_dense, V);
+    return hipGetLastError();
 }
 
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
@@ -853,8 +962,7 @@ hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingPar
 
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
     const int rows_per_seq = sp.init_mode >= 3 ? 2 * d.L : d.L;
-    draw_kernel<<<n_seqs * rows_per_seq, d.V >= 8192 ? 1024 : 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq,
-                                                                                                 sp.init_mode, sp.row_width);
+    draw_kernel<<<n_seqs * rows_per_seq, 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq, sp.init_mode, sp.row_width);
     return hipGetLastError();
 }
 

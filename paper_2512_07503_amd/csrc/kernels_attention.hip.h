@@ -121,9 +121,6 @@ struct AttnArgs {
     bf16_t *out_act;         // [M][H * hd] GEMM-operand layout
     float *out_plain;        // optional [M][H][hd]
     int L, H, Hkv, hd, chunk, n_chunks;
-#ifdef SJD_PHASE_TIMING
-    unsigned long long *phase;  // [workgroups][8] wall-clock stamps (profiling builds only)
-#endif
     int n_qt;                // query tiles of 32 window rows = ceil(L / 32)
     float scale_log2e;       // 1 / sqrt(hd) * log2(e)
 };
@@ -301,16 +298,9 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
     const int kv = a.seg_kv[seg];
     const int n_tot = n_act > 0 ? kv + n_act : 0;
     const int n_vis = 32 * qt < n_act ? min(n_tot, kv + 32 * (qt + 1)) : 0;  // nothing later is visible to this query tile
-#ifdef SJD_PHASE_TIMING
-#define SJD_ATTN_STAMP(i) do { if (a.phase && threadIdx.x == 0) a.phase[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SJD_ATTN_STAMP(i) do { } while (0)
-#endif
-    SJD_ATTN_STAMP(0);
     f32x16 o[DB];
     float m_run, l_run;
     attention_wave<HD, (HD <= 64 ? 3 : 1)>(a, seg, h, kvh, qt, 32 * wave, n_vis, 32 * NS, kv, n_tot, lane, o, m_run, l_run);
-    SJD_ATTN_STAMP(1);
     const int query = lane & 31;
     l_run += __shfl_xor(l_run, 32, 64);
 
@@ -333,7 +323,6 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
     const bool row = 32 * qt + query < a.L;
     const bool active = row && a.row_tok[m] >= 0 && denom > 0.0f;
     const float inv = active ? 1.0f / denom : 0.0f;
-    SJD_ATTN_STAMP(2);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
         __syncthreads();
@@ -354,7 +343,6 @@ __global__ __launch_bounds__(NS * 64) void attention_onepass_kernel(AttnArgs a) 
             }
         }
     }
-    SJD_ATTN_STAMP(3);
 }
 
 // Merges the chunks of every (row, head): out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.

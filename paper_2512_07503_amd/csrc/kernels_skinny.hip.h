@@ -43,6 +43,7 @@ struct SkinnyArgs {
     const bf16_t *A;   // [MT][KB][64][8] raw activations, fragment-major
     const bf16_t *W;   // [groups * NBW][KB][64][8]
     int M, KB;
+    int n_cus;         // compute units of the device (launch heuristics on the host)
     int groups;        // column groups (set by the launcher)
     int m_groups;      // row groups of MT * 32 rows, each run by its own workgroups over the same weights (M > 64)
     int row_split;     // 2: (one 32-row tile, whole K) two workgroups per column group, 16 rows each; else 1
@@ -85,9 +86,6 @@ struct SkinnyArgs {
     KvPool kv_pool;             // the pools of the layer whose attention comes next
     int kv_pairs;               // segments * H
     const int32_t *kv_seg_kv;   // [segments] tokens in the cache before this forward's rows
-#ifdef SJD_PHASE_TIMING
-    unsigned long long *phase;  // [groups][8] wall-clock stamps of workgroup phases (profiling builds only)
-#endif
 };
 
 SJD_D QkvRow qkv_row(const SkinnyArgs &a, int m) { return a.row_meta[m]; }
@@ -291,12 +289,6 @@ SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
         const int r = it + rot;
         return (size_t)(kb_lo + wave + (r >= n_it ? r - n_it : r) * NW);
     };
-#ifdef SJD_PHASE_TIMING
-#define SJD_STAMP(i) do { if (a.phase && tid == 0) a.phase[g * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SJD_STAMP(i) do { } while (0)
-#endif
-    SJD_STAMP(0);
 
     // What the epilogue will need from memory is requested now, ahead of the weight stream, so that its latency
     // is not paid after the last MFMA: residual values (RESID), row destination and rotation (QKV).  Thread t ends
@@ -408,7 +400,6 @@ SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
             if (it0 + DEPTH + s < n_it) consume(s);
     }
 
-    SJD_STAMP(1);
     // ---- sum the NW partial tiles through LDS; thread t ends up with elements e = t and t + 512 of every
     //      tile: accumulator register v = e / 64 of lane l = e % 64, i.e. row 8 (v / 4) + 4 (l / 32) + v % 4,
     //      column l % 32.
@@ -440,7 +431,6 @@ SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
             }
         }
 
-    SJD_STAMP(2);
     const int col = lane & 31;
 #pragma unroll
     for (int j = 0; j < MT; ++j)
@@ -466,7 +456,6 @@ SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
             if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[j][hh], g, col, vals[0] * inv, vals[NBW - 1] * inv, rot_c[j][hh], rot_s[j][hh]);
             else skinny_epilogue<EPI, NBW>(a, ks, m, blk0, col, vals, inv, xin);
         }
-    SJD_STAMP(3);
 }
 
 // Embedding gather for the fused path: fp32 residual stream + its bf16 fragment-major copy.  The block of row m
@@ -600,10 +589,10 @@ inline hipError_t launch_skinny_nw(hipStream_t st, const SkinnyArgs &a_in, int M
     return hipGetLastError();
 }
 
-// More than 256 column groups of two blocks, one row group, whole K, 4 wavefronts: 256 workgroups (groups <= 512),
-// the first groups - 256 of them two groups wide; beyond 512 groups every workgroup is two groups wide.
+// More column groups (of two blocks) than CUs, one row group, whole K, 4 wavefronts: one workgroup per CU (up to twice as
+// many groups as CUs), the first groups - CUs of them two groups wide; beyond that every workgroup is two groups wide.
 inline bool skinny_mixed_applies(const SkinnyArgs &a, int groups, int nbw, int nw) {
-    return groups > 256 && nbw == 2 && nw == 4 && a.m_groups <= 1 && a.ksplit == 1 && a.row_split != 2;
+    return groups > a.n_cus && nbw == 2 && nw == 4 && a.m_groups <= 1 && a.ksplit == 1 && a.row_split != 2;
 }
 template <int EPI>
 inline hipError_t launch_skinny_mixed(hipStream_t st, const SkinnyArgs &a_in, int MT, int groups) {
@@ -612,7 +601,7 @@ inline hipError_t launch_skinny_mixed(hipStream_t st, const SkinnyArgs &a_in, in
     if (!skinny_mixed_applies(a, groups, 2, 4) || MT < 1 || MT > 2) return hipErrorInvalidValue;
     a.groups = groups;
     a.pf_wgs = a.kv_wgs = 0;
-    a.n_heavy = std::min(groups / 2, groups - 256);
+    a.n_heavy = std::min(groups / 2, groups - a.n_cus);
     const int light = groups - 2 * a.n_heavy;
     if (MT == 1) gemm_skinny_mixed_kernel<1, 4, DEPTH, EPI><<<a.n_heavy + light, 256, 0, st>>>(a);
     else gemm_skinny_mixed_kernel<2, 4, DEPTH, EPI><<<a.n_heavy + light, 256, 0, st>>>(a);

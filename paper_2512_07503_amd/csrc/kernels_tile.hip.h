@@ -226,12 +226,12 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
 // the fewest operand bytes per MFMA: 0.75 KiB against 1.25 KiB for 128 rows, whose weight fragments alone would
 // take the whole LDS bandwidth at full MFMA rate.  128 rows are chosen where they spread the work better: when
 // 256-row tiles would not even fill the CUs, or when the most loaded CU (a launch takes as long as that one)
-// gets less work - ceil(workgroups / 256) tiles of 256 rows against as many half-size ones.
-inline int tile_rows_for(int M, int n_blocks, int ksplit) {
+// gets less work - ceil(workgroups / CUs) tiles of 256 rows against as many half-size ones.
+inline int tile_rows_for(int M, int n_blocks, int ksplit, int n_cus) {
     const int col_tiles = (n_blocks + 3) / 4;
     const long wg2 = (long)col_tiles * ((M + 255) / 256) * ksplit, wg1 = (long)col_tiles * ((M + 127) / 128) * ksplit;
-    if (wg2 < 256) return 128;
-    const long cost2 = 2 * ((wg2 + 255) / 256), cost1 = (wg1 + 255) / 256;
+    if (wg2 < n_cus) return 128;
+    const long cost2 = 2 * ((wg2 + n_cus - 1) / n_cus), cost1 = (wg1 + n_cus - 1) / n_cus;
     return cost1 < cost2 ? 128 : 256;
 }
 
@@ -240,7 +240,7 @@ template <int EPI>
 inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks, int tile_rows = 0) {
     if (a.M <= 0 || n_blocks <= 0 || a.KB <= 0 || a.ksplit < 1 || (size_t)a.kb_per_split * a.ksplit < (size_t)a.KB) return hipErrorInvalidValue;
     if (EPI != EPI_PARTIAL && a.ksplit != 1) return hipErrorInvalidValue;
-    if (tile_rows == 0) tile_rows = tile_rows_for(a.M, n_blocks, a.ksplit);
+    if (tile_rows == 0) tile_rows = tile_rows_for(a.M, n_blocks, a.ksplit, a.n_cus > 0 ? a.n_cus : 256);
     const int row_tiles32 = (a.M + 31) / 32, row_tiles = (a.M + tile_rows - 1) / tile_rows, col_tiles = (n_blocks + 3) / 4;
     const dim3 grid(8 * ((col_tiles + 7) / 8) * row_tiles, a.ksplit);
     constexpr bool kNorm = EPI != EPI_RESID && EPI != EPI_PARTIAL;

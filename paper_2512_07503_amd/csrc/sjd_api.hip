@@ -63,6 +63,7 @@ struct sjd_ctx {
     hipStream_t stream = nullptr;
     char err[512] = "";
     int hd = 0, Vs = 0, L = 0, S = 0, n_seqs = 0, pt = 0, pps = 0, n_pages = 0, max_visible = 0;
+    int n_cus = 256, n_xcds = 8;   // compute units and XCDs (L2 domains) of the device, read at create
     bool prefilled = false, all_done = false;
     // one sjd_step = the same launch sequence with the same arguments every time (what changes lives in device
     // memory): captured once per batch size into a HIP graph and replayed
@@ -92,6 +93,7 @@ struct sjd_ctx {
     size_t pool_layer_bytes = 0;
     int32_t *page_table = nullptr;
     std::vector<int32_t> page_table_host;  // what sjd_prefill uploaded (snapshots carry it)
+    std::vector<int32_t> n_image_host;     // image tokens wanted per sequence of the current batch
     // workspaces
     float *x = nullptr, *partial = nullptr, *logits = nullptr;
     void *xn = nullptr, *q = nullptr, *attn = nullptr, *h = nullptr;
@@ -305,6 +307,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     // up to 64 rows: one row group; more (a multiple of 64 by construction): row groups of 64 over the same weights
     const int m_groups = M <= 64 ? 1 : M / 64;
     const int MT = M <= 64 ? ceil_div(M, 32) : 2;
+    const int n_cus = c->n_cus;
     hipStream_t st = c->stream;
     SJD_LAUNCH(c, KC_EMBED, after([&] {
                    RowTables rt;
@@ -317,6 +320,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     SkinnyArgs a;
     memset(&a, 0, sizeof a);
     a.M = M;
+    a.n_cus = n_cus;
     a.m_groups = m_groups;
     a.eps = md.rms_eps;
     a.row_meta = c->row_meta;
@@ -353,7 +357,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     // own: row groups of 32 rows instead of 64 (all row groups of a column group on one XCD, whose L2 serves the
     // later readers of the weights).  Each workgroup pulls half the activations, twice as many CUs work.
     auto rows2_for = [&](int groups) {
-        return MT == 2 && 2 * m_groups * 8 * ceil_div(groups, 8) <= 256 && !(md.kernel_flags & SJD_NO_ROW_SPLIT);
+        return MT == 2 && 2 * m_groups * 8 * ceil_div(groups, 8) <= n_cus && !(md.kernel_flags & SJD_NO_ROW_SPLIT);
     };
     // computing workgroups of a launch over `groups` column groups
     auto compute_wgs = [&](int groups, bool r2, int row_split) {
@@ -369,7 +373,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         const uint32_t slab = (uint32_t)nx.nbw * nx.KB * 1024;
         int fit = (int)std::min<size_t>(nx.groups, ((size_t)24 << 20) / slab);   // what the L2s hold beside the current weights
         int wgs = (int)(((size_t)fit * slab / (96 << 10) + 7) / 8 * 8);
-        wgs = std::min(wgs, (256 - cur_groups) / 8 * 8);
+        wgs = std::min(wgs, (n_cus - cur_groups) / 8 * 8);
         if (wgs < 8 || (m_groups > 1 && wgs < 32)) return;   // long-window launches: a handful of CUs only delays them
         // few CUs left: touch no more than they get through while the launch computes (a CU streams ~45 GB/s from
         // HBM, the launches take 7-10 us: 320 KB each), the first slabs
@@ -378,12 +382,12 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.pf_base = (const char *)nx.W; a.pf_slab_bytes = slab; a.pf_groups = fit; a.pf_wgs = wgs; a.pf_sink = c->pf_sink;
     };
     // The same for the keys and values of the next one-pass attention launch (one workgroup per (head, segment), in
-    // that order); call after warm(): takes what is left of the 256 CUs.
+    // that order); call after warm(): takes what is left of the CUs.
     auto warm_kv = [&](int cur_groups, const KvPool &pool) {
         a.kv_wgs = 0;
         if (!c->l2_warm || tile || m_groups > 1 || !c->attn_mfma || !c->attn_onepass || c->L > 32) return;
         const size_t kv_bytes = (size_t)(M / c->L) * Hkv * md.max_ctx * hd * 2 * sizeof(bf16_t);
-        const int room = (256 - cur_groups - a.pf_wgs) / 8 * 8;
+        const int room = (n_cus - cur_groups - a.pf_wgs) / 8 * 8;
         a.kv_wgs = std::max(0, std::min(room, (int)((kv_bytes / (48 << 10) + 7) / 8 * 8)));
         a.kv_pairs = (M / c->L) * H;
         a.kv_seg_kv = c->rm.seg_kv;
@@ -408,7 +412,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         a.row_ssq_part = nullptr;
         if (tile) {
             const int n_blocks = ceil_div(d, 64) * 2, wgs = ceil_div(n_blocks, 4) * ceil_div(M, TILE_M);
-            int ks = std::min(8, std::max(1, 256 / wgs));
+            int ks = std::min(8, std::max(1, n_cus / wgs));
             while (ks > 1 && a.KB / ks < 32) --ks;
             a.kb_per_split = ceil_div(a.KB, ks);
             a.ksplit = ceil_div(a.KB, a.kb_per_split);
@@ -430,7 +434,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         const double wg_bytes = (double)(nbw_d * 32 + mt_resid * 32) * K * 2.0;
         int ks = 1;
         if (wg_bytes > 512e3) {
-            ks = std::min(8, std::max(1, 256 / (groups * m_groups)));
+            ks = std::min(8, std::max(1, n_cus / (groups * m_groups)));
             while (ks > 1 && a.KB / ks < 32) --ks;
         }
         if (ks == 1) {
@@ -719,15 +723,24 @@ int alloc_state(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &d.acc_len, (size_t)S * 4))) return rc;
     if ((rc = dev_alloc(c, &d.cand, (size_t)S * L * 4))) return rc;
     if ((rc = dev_alloc(c, &d.cand_new, (size_t)S * L * 4))) return rc;
+    d.cap = c->Vs;   // room for a whole row of kept pairs (ties at the K-th value can keep everything); pages that are never
+                     // written are never touched
     if (c->sp.init_mode == 4) {
-        if ((rc = dev_alloc(c, &d.hist_e, (size_t)S * c->sp.row_width * c->Vs * sizeof(float)))) return rc;
-        if ((rc = dev_alloc(c, &d.hist_Z, (size_t)S * c->sp.row_width * sizeof(uint64_t)))) return rc;
+        const size_t rows = (size_t)S * c->sp.row_width;
+        if ((rc = dev_alloc(c, &d.hist_ids, rows * d.cap * sizeof(int32_t), false))) return rc;
+        if ((rc = dev_alloc(c, &d.hist_e, rows * d.cap * sizeof(float), false))) return rc;
+        if ((rc = dev_alloc(c, &d.hist_cnt, rows * sizeof(int32_t)))) return rc;
+        if ((rc = dev_alloc(c, &d.hist_Z, rows * sizeof(uint64_t)))) return rc;
     }
     if ((rc = dev_alloc(c, &d.step, 4))) return rc;
     for (int b = 0; b < 2; ++b) {
-        if ((rc = dev_alloc(c, &d.e_buf[b], (size_t)S * L * c->Vs * sizeof(float)))) return rc;
+        if ((rc = dev_alloc(c, &d.ids_buf[b], (size_t)S * L * d.cap * sizeof(int32_t), false))) return rc;
+        if ((rc = dev_alloc(c, &d.e_buf[b], (size_t)S * L * d.cap * sizeof(float), false))) return rc;
+        if ((rc = dev_alloc(c, &d.cnt_buf[b], (size_t)S * L * sizeof(int32_t)))) return rc;
         if ((rc = dev_alloc(c, &d.Z_buf[b], (size_t)S * L * sizeof(uint64_t)))) return rc;
     }
+    if ((rc = dev_alloc(c, &d.allow_lo, (size_t)S * d.max_img * 4))) return rc;
+    if ((rc = dev_alloc(c, &d.allow_hi, (size_t)S * d.max_img * 4))) return rc;
     if ((rc = dev_alloc(c, &d.res, (size_t)S * sizeof(sjd_step_result)))) return rc;
     if ((rc = dev_alloc(c, &c->prompt_dev, (size_t)S * 2 * c->md.max_ctx * 4))) return rc;
     if ((rc = dev_alloc(c, &c->prompt_len_dev, (size_t)S * 2 * 4))) return rc;
@@ -867,6 +880,14 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
     c->sp.seed = sampling->seed;
     c->sp.init_mode = sampling->init_mode;
     c->sp.row_width = sampling->row_width;
+    {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) c->n_cus = v;
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeNumberOfXccs, dev) == hipSuccess && v > 0) c->n_xcds = v;
+        }
+        (void)hipGetLastError();
+    }
     const bool f32 = desc->dtype == SJD_F32;
     c->use_graph = !(desc->kernel_flags & SJD_NO_GRAPH) && hip_stream != nullptr;  // the default stream cannot be captured
     c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&
@@ -953,6 +974,7 @@ int sjd_prefill(sjd_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, cons
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->page_table, table.data(), table.size() * 4, hipMemcpyHostToDevice, st));
     SJD_HIP_TRY(c->err, hipStreamSynchronize(st));  // the host staging vectors may go away on an early return
     c->page_table_host = table;
+    c->n_image_host.assign(n_image_tokens, n_image_tokens + n_seqs);
     const int chunks = ceil_div(max_prompt - 1, L);
     for (int ch = 0; ch < chunks; ++ch) {
         SJD_LAUNCH(c, KC_STAGE, launch_stage_prompt(st, c->rm, c->prompt_dev, c->prompt_len_dev, max_prompt, ch, L, n_seqs));
@@ -1041,6 +1063,31 @@ int sjd_get_window(sjd_ctx *c, int32_t seq, int32_t *tokens, int32_t *ref_rows, 
     return SJD_OK;
 }
 
+int sjd_set_token_ranges(sjd_ctx *c, int32_t seq, const int32_t *first_id, const int32_t *end_id, int32_t n_positions) {
+    if (!c) return SJD_EINVAL;
+    if (!c->prefilled) { sjd_set_error(c->err, "sjd_set_token_ranges before sjd_prefill"); return SJD_ESTATE; }
+    if (seq < 0 || seq >= c->n_seqs || !first_id || !end_id || n_positions < 0 || (size_t)seq >= c->n_image_host.size() ||
+        n_positions > c->n_image_host[seq]) {
+        sjd_set_error(c->err, "bad sequence index, null array or more positions than image tokens");
+        return SJD_EINVAL;
+    }
+    std::vector<int32_t> lo(n_positions), hi(n_positions);
+    for (int i = 0; i < n_positions; ++i) {
+        if (first_id[i] < c->md.sample_lo || end_id[i] > c->md.sample_hi || first_id[i] >= end_id[i]) {
+            sjd_set_error(c->err, "position %d: id range [%d, %d) is empty or leaves the sampled ids", i, first_id[i], end_id[i]);
+            return SJD_EINVAL;
+        }
+        lo[i] = first_id[i] - c->md.sample_lo;
+        hi[i] = end_id[i] - c->md.sample_lo;
+    }
+    SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
+    if (n_positions > 0) {
+        SJD_HIP_TRY(c->err, hipMemcpy(c->ds.allow_lo + (size_t)seq * c->ds.max_img, lo.data(), (size_t)n_positions * 4, hipMemcpyHostToDevice));
+        SJD_HIP_TRY(c->err, hipMemcpy(c->ds.allow_hi + (size_t)seq * c->ds.max_img, hi.data(), (size_t)n_positions * 4, hipMemcpyHostToDevice));
+    }
+    return SJD_OK;
+}
+
 int sjd_trace_enable(sjd_ctx *c, int32_t on) {
     if (!c) return SJD_EINVAL;
     c->tracer.on = on != 0;
@@ -1086,14 +1133,20 @@ struct StateArray { void *p; size_t per_seq; };
 std::vector<StateArray> state_arrays(sjd_ctx *c) {
     const DecideState &d = c->ds;
     const size_t L = c->L, V = c->Vs;
+    const size_t cap = d.cap;
     std::vector<StateArray> a = {
         {d.win_tok, L * 4}, {d.anchor, 8}, {d.ref_row, L * 4}, {d.n_img, 4}, {d.n_image, 4}, {d.kv_len, 8}, {d.Le, 4},
         {d.out_tok, (size_t)d.max_img * 4}, {d.acc_len, 4}, {d.cand, L * 4}, {d.cand_new, L * 4},
-        {d.e_buf[0], L * V * 4}, {d.e_buf[1], L * V * 4}, {d.Z_buf[0], L * 8}, {d.Z_buf[1], L * 8}, {d.res, sizeof(sjd_step_result)}};
+        {d.ids_buf[0], L * cap * 4}, {d.ids_buf[1], L * cap * 4}, {d.e_buf[0], L * cap * 4}, {d.e_buf[1], L * cap * 4},
+        {d.cnt_buf[0], L * 4}, {d.cnt_buf[1], L * 4}, {d.Z_buf[0], L * 8}, {d.Z_buf[1], L * 8},
+        {d.allow_lo, (size_t)d.max_img * 4}, {d.allow_hi, (size_t)d.max_img * 4}, {d.res, sizeof(sjd_step_result)}};
     if (c->sp.init_mode == 4) {
-        a.push_back({d.hist_e, (size_t)c->sp.row_width * V * 4});
+        a.push_back({d.hist_ids, (size_t)c->sp.row_width * cap * 4});
+        a.push_back({d.hist_e, (size_t)c->sp.row_width * cap * 4});
+        a.push_back({d.hist_cnt, (size_t)c->sp.row_width * 4});
         a.push_back({d.hist_Z, (size_t)c->sp.row_width * 8});
     }
+    (void)V;
     return a;
 }
 size_t snapshot_header_bytes(int n_seqs) { return (sizeof(SnapshotHeader) + (size_t)(2 * n_seqs) * 4 + 15) / 16 * 16; }

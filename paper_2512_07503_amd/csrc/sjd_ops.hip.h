@@ -249,14 +249,29 @@ int sjd_op_window_attention(void *hip_stream, int32_t dtype, int32_t flags, cons
 }
 
 int sjd_op_sampling_rows(void *hip_stream, const float *logits_c, const float *logits_u, float *e, uint64_t *Z, int32_t rows,
-                         int32_t V, float cfg_scale, float temperature, int32_t top_k, int32_t repeat, float *avg_ms) {
-    if (!logits_c || !logits_u || !e || !Z || rows < 1 || V < 1 || top_k < 1 || !(temperature > 0.0f) || repeat < 1) {
+                         int32_t V, float cfg_scale, float temperature, int32_t top_k, const int32_t *allow_lo,
+                         const int32_t *allow_hi, int32_t *kept_ids, int32_t *kept_cnt, int32_t repeat, float *avg_ms) {
+    if (!logits_c || !logits_u || !e || !Z || rows < 1 || V < 1 || top_k < 1 || !(temperature > 0.0f) || repeat < 1 ||
+        (allow_lo == nullptr) != (allow_hi == nullptr)) {
         sjd_set_error(g_create_error, "bad argument");
         return SJD_EINVAL;
     }
     hipStream_t st = (hipStream_t)hip_stream;
     Scratch s;
-    if (!s.events()) return SJD_ENOMEM;
+    int32_t *ids, *cnt;
+    float *ev;
+    if (!s.events() || !s.alloc(&ids, (size_t)rows * V * 4, st) || !s.alloc(&ev, (size_t)rows * V * 4, st) ||
+        !s.alloc(&cnt, (size_t)rows * 4, st)) {
+        sjd_set_error(g_create_error, "allocation failed");
+        return SJD_ENOMEM;
+    }
+    if (allow_lo) {   // the ranges are the caller's: check them before a kernel indexes with them
+        std::vector<int32_t> lo(rows), hi(rows);
+        OP_TRY(hipMemcpy(lo.data(), allow_lo, (size_t)rows * 4, hipMemcpyDeviceToHost));
+        OP_TRY(hipMemcpy(hi.data(), allow_hi, (size_t)rows * 4, hipMemcpyDeviceToHost));
+        for (int r = 0; r < rows; ++r)
+            if (lo[r] < 0 || hi[r] > V || lo[r] >= hi[r]) { sjd_set_error(g_create_error, "row %d: bad id range", r); return SJD_EINVAL; }
+    }
     SamplingParams sp;
     sp.cfg_scale = cfg_scale;
     sp.inv_temperature = 1.0f / temperature;
@@ -264,8 +279,13 @@ int sjd_op_sampling_rows(void *hip_stream, const float *logits_c, const float *l
     sp.top_k = top_k;
     sp.seed = 0;
     OP_TRY(hipEventRecord(s.ev0, st));
-    for (int r = 0; r < repeat; ++r) OP_TRY(launch_sampling_rows_plain(st, logits_c, logits_u, e, Z, rows, V, sp));
+    for (int r = 0; r < repeat; ++r) OP_TRY(launch_sampling_rows_plain(st, logits_c, logits_u, ids, ev, cnt, Z, rows, V, sp, allow_lo, allow_hi));
     OP_TRY(hipEventRecord(s.ev1, st));
+    // the dense form of the rows: zeros, then the kept pairs
+    OP_TRY(hipMemsetAsync(e, 0, (size_t)rows * V * sizeof(float), st));
+    OP_TRY(launch_scatter_rows(st, ids, ev, cnt, e, rows, V));
+    if (kept_ids) OP_TRY(hipMemcpyAsync(kept_ids, ids, (size_t)rows * V * 4, hipMemcpyDeviceToDevice, st));
+    if (kept_cnt) OP_TRY(hipMemcpyAsync(kept_cnt, cnt, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
     OP_TRY(hipStreamSynchronize(st));
     if (avg_ms) {
         float ms = 0.0f;

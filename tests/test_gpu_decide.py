@@ -10,11 +10,15 @@ from helpers import make_pair, assert_same_state
 pytestmark = pytest.mark.gpu
 
 
-def _drive(oracle, cfg_name, n_steps, window, n_image, n_seqs, top_k, tau, seed, scale, drift, prompt_len=4):
+def _drive(oracle, cfg_name, n_steps, window, n_image, n_seqs, top_k, tau, seed, scale, drift, prompt_len=4, ranges=None):
     cfg = workload.get_config(cfg_name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=window, n_image=n_image, prompt_len=prompt_len, n_seqs=n_seqs,
                                           top_k=top_k, tau=tau, seed=seed, n_layers=1)
     S, L, Vs = n_seqs, window, o.Vs
+    if ranges is not None:
+        for s in range(S):
+            first, end = ranges(s, n_img[s], cfg["arch"])
+            assert o.set_token_ranges(s, first, end) == 0 and g.set_token_ranges(s, first, end) == 0
     rng = np.random.default_rng(seed + 99)
     Nmax = max(n_img)
     base = (rng.standard_normal((S, 2, Nmax + L, Vs)) * scale).astype(np.float32)   # a row per absolute image position
@@ -50,6 +54,37 @@ def _drive(oracle, cfg_name, n_steps, window, n_image, n_seqs, top_k, tau, seed,
 def test_decisions_bit_exact_small(oracle, name, L, N, S, K, tau, seed, scale, drift):
     st = _drive(oracle, name, 400, L, N, S, K, tau, seed, scale, drift)
     assert st["steps"] > 0
+
+
+@pytest.mark.parametrize("name,L,N,S,K,tau,seed", [("small_f32", 8, 60, 2, 50, 0.5, 11), ("small_sub", 5, 30, 3, 40, 0.5, 12),
+                                                    ("small_f32", 1, 20, 1, 50, 0.5, 13), ("small_f32", 16, 45, 1, 600, float("inf"), 14)])
+def test_forced_token_ranges_bit_exact(oracle, name, L, N, S, K, tau, seed):
+    """Token ranges per image position (a forced end-of-row token every 7 positions, a sub-range elsewhere, the
+    tail of the image unrestricted; different ranges per sequence): decisions and windows identical to the
+    oracle's, and the forced tokens come out where they were forced."""
+    def ranges(s, n, arch):
+        lo0, hi0 = arch["sample_lo"], arch["sample_hi"]
+        m = n - 3                                              # the last three positions keep the whole range
+        eol = lo0 + 3 + s
+        first = np.array([eol if (i + 1) % 7 == 0 else lo0 + 10 * (s + 1) for i in range(m)], dtype=np.int32)
+        end = np.array([eol + 1 if (i + 1) % 7 == 0 else hi0 - 5 * s for i in range(m)], dtype=np.int32)
+        return first, end
+    st = _drive(oracle, name, 400, L, N, S, K, tau, seed, 2.0, 0.3, ranges=ranges)
+    assert st["steps"] > 0
+
+
+def test_token_range_errors(oracle):
+    cfg = workload.get_config("small_f32")
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=4, n_image=10, prompt_len=4, n_layers=1)
+    lo0, hi0 = cfg["arch"]["sample_lo"], cfg["arch"]["sample_hi"]
+    ok_lo, ok_hi = np.full(10, lo0, np.int32), np.full(10, hi0, np.int32)
+    assert g.set_token_ranges(0, ok_lo, ok_hi) == 0
+    assert g.set_token_ranges(1, ok_lo, ok_hi) == -1                                  # no such sequence
+    assert g.set_token_ranges(0, ok_hi, ok_hi) == -1                                  # empty range
+    assert g.set_token_ranges(0, ok_lo, ok_hi + 1) == -1                              # beyond the sampled ids
+    assert g.set_token_ranges(0, np.full(11, lo0, np.int32), np.full(11, hi0, np.int32)) == -1   # more positions than image tokens
+    g.decode(100)
+    assert len(g.tokens(0)) == 10
 
 
 def test_decisions_bit_exact_cfg0_shape(oracle):

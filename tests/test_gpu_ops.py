@@ -35,7 +35,11 @@ def test_philox_matches_oracle_on_a_million_counters(sjd, oracle):
 
 @pytest.mark.parametrize("V,K,s,T,scale", [(8, 6, 3.0, 1.0, 1.0), (100, 7, 3.0, 1.0, 2.0), (1000, 100, 3.0, 1.0, 3.0),
                                             (4096, 256, 3.0, 1.0, 3.0), (4097, 4097, 1.5, 0.7, 1.0), (300, 1000, 0.0, 2.0, 5.0),
-                                            (16384, 1000, 3.0, 1.0, 3.0), (65536, 2000, 3.0, 1.0, 2.0), (32768, 1, 3.0, 1.0, 2.0)])
+                                            (16384, 1000, 3.0, 1.0, 3.0), (65536, 2000, 3.0, 1.0, 2.0), (32768, 1, 3.0, 1.0, 2.0),
+                                            # wider than the register-resident kernel takes (64 x 1024 ids): the multi-pass kernel
+                                            (70001, 2000, 3.0, 1.0, 2.0), (66000, 70000, 3.0, 1.0, 1.0),
+                                            # K just below V, K = 2: thresholds at both ends of the row
+                                            (4096, 4095, 3.0, 1.0, 3.0), (16384, 2, 3.0, 1.0, 3.0), (32768, 2048, 3.0, 0.05, 2.0)])
 def test_sampling_rows_bit_exact(sjd, oracle, V, K, s, T, scale):
     import torch
     rng = np.random.default_rng(V * 7 + K)
@@ -46,12 +50,37 @@ def test_sampling_rows_bit_exact(sjd, oracle, V, K, s, T, scale):
     lu[1, : V // 2] = np.round(lu[1, : V // 2])
     lc[2] = lu[2]                                   # guidance is the identity
     lc[3] *= 30.0                                   # exponent underflow region (z - max < -60)
-    e, Z, _ = sjd.op_sampling_rows(torch.from_numpy(lc).cuda(), torch.from_numpy(lu).cuda(), s, T, K)
-    e, Z = e.cpu().numpy(), Z.cpu().numpy().view(np.uint64)
+    e, Z, _, ids, cnt = sjd.op_sampling_rows(torch.from_numpy(lc).cuda(), torch.from_numpy(lu).cuda(), s, T, K, kept=True)
+    e, Z, ids, cnt = e.cpu().numpy(), Z.cpu().numpy().view(np.uint64), ids.cpu().numpy(), cnt.cpu().numpy()
     for r in range(rows):
         e_ref, Z_ref = oracle.sampling_row(lc[r], lu[r], s, T, K)
         assert np.array_equal(e[r].view(np.uint32), e_ref.view(np.uint32)), (r, np.flatnonzero(e[r] != e_ref)[:5])
         assert int(Z[r]) == Z_ref
+        # the stored form of the row: ascending ids, every id with a weight among them, at least min(K, V) of them
+        kept = ids[r, : cnt[r]]
+        assert min(K, V) <= cnt[r] <= V and (np.diff(kept) > 0).all() and kept[0] >= 0 and kept[-1] < V
+        assert np.isin(np.flatnonzero(e_ref), kept).all()
+
+
+@pytest.mark.parametrize("V,K", [(1000, 100), (16384, 1000), (65536, 2000), (70001, 500)])
+def test_sampling_rows_with_token_ranges_bit_exact(sjd, oracle, V, K):
+    import torch
+    rng = np.random.default_rng(V + K)
+    ranges = [(0, V), (0, 1), (V - 1, V), (V // 3, V // 3 + K), (5, V - 7), (V // 2, V // 2 + K // 2), (V // 4 - 1, V // 4 + 1)]
+    rows = len(ranges)
+    lc = (rng.standard_normal((rows, V)) * 2).astype(np.float32)
+    lu = (rng.standard_normal((rows, V)) * 2).astype(np.float32)
+    lo = torch.tensor([a for a, _ in ranges], dtype=torch.int32).cuda()
+    hi = torch.tensor([b for _, b in ranges], dtype=torch.int32).cuda()
+    e, Z, _, ids, cnt = sjd.op_sampling_rows(torch.from_numpy(lc).cuda(), torch.from_numpy(lu).cuda(), 3.0, 1.0, K,
+                                             allow_lo=lo, allow_hi=hi, kept=True)
+    e, Z, ids, cnt = e.cpu().numpy(), Z.cpu().numpy().view(np.uint64), ids.cpu().numpy(), cnt.cpu().numpy()
+    for r, (a, b) in enumerate(ranges):
+        e_ref, Z_ref = oracle.sampling_row(lc[r], lu[r], 3.0, 1.0, K, allow=(a, b))
+        assert np.array_equal(e[r].view(np.uint32), e_ref.view(np.uint32)), (r, a, b)
+        assert int(Z[r]) == Z_ref
+        kept = ids[r, : cnt[r]]
+        assert cnt[r] == min(K, b - a) and kept.min() >= a and kept.max() < b
 
 
 def _gemm_case(sjd, M, N, K, dtype, flags, splits=0):

@@ -324,6 +324,97 @@ def test_reuse_threshold_semantics(oracle, tau):
     assert seen_redraw > 0 if tau != 0.0 else seen_keep > 0
 
 
+def test_forced_tokens_appear_where_they_are_forced(oracle):
+    """Token ranges (sjd.h: forced tokens): a range of one id forces that token at its position for every seed and
+    window, the other positions stay inside their ranges, and with L = 1 the decode is ancestral sampling from the
+    masked distributions (recomputed with the masked row primitive and the same counters)."""
+    cfg, arch, w, cond, uncond = _model("small_f32")
+    lo0, hi0, N, K = arch["sample_lo"], arch["sample_hi"], 20, 50
+    eol = lo0 + 7
+    first = np.array([eol if (i + 1) % 5 == 0 else lo0 + 8 for i in range(N)], dtype=np.int32)
+    end = np.array([eol + 1 if (i + 1) % 5 == 0 else hi0 for i in range(N)], dtype=np.int32)
+    for L, seed in [(1, 3), (4, 4), (6, 5), (6, 6)]:
+        dec = oracle.Oracle(arch, w, L, cfg["prompt_len"] + N, top_k=K, seed=seed)
+        assert dec.prefill(cond, uncond, [N]) == 0
+        assert dec.set_token_ranges(0, first, end) == 0
+        hist = dec.decode()
+        toks = dec.tokens()
+        assert len(toks) == N and sum(h[0]["n_finalized"] for h in hist) == N
+        for i in range(N):
+            assert first[i] <= toks[i] < end[i], (L, i, toks[i])
+        if L == 1:
+            c, u = list(cond[0]), list(uncond[0])
+            for i in range(N):
+                lc, lu = oracle.forward_logits(arch, w, c)[-1], oracle.forward_logits(arch, w, u)[-1]
+                e, Z = oracle.sampling_row(lc, lu, 3.0, 1.0, K, allow=(int(first[i]) - lo0, int(end[i]) - lo0))
+                words = oracle.philox([i + 1, 0, 0, 0], [seed, 0])
+                assert toks[i] == lo0 + oracle.draw(e, Z, (words[1] << 32) | words[2]), i
+                c.append(int(toks[i]))
+                u.append(int(toks[i]))
+    dec = oracle.Oracle(arch, w, 4, cfg["prompt_len"] + N, top_k=K)
+    assert dec.set_token_ranges(0, first, end) == -3                     # before prefill
+    dec.prefill(cond, uncond, [N])
+    assert dec.set_token_ranges(0, first, first) == -1                   # empty ranges
+    assert dec.set_token_ranges(1, first, end) == -1                     # no such sequence
+    assert dec.set_token_ranges(0, np.zeros(N + 1, np.int32), np.ones(N + 1, np.int32)) == -1
+
+
+def test_each_branch_starts_from_its_own_last_prompt_token(oracle):
+    """First step with prompts that END differently: row k of each branch must be the model's prediction after that
+    branch's own prompt followed by the drafts (recomputed with the plain full-sequence forward)."""
+    cfg, arch, w, cond, uncond = _model("small_f32")
+    c, u = np.array(cond[0]), np.array(uncond[0][:-3])
+    u[-1] = (c[-1] + 5) % arch["vocab"]
+    assert c[-1] != u[-1] and len(c) != len(u)
+    L, N = 4, 10
+    dec = oracle.Oracle(arch, w, L, len(c) + N, top_k=30, seed=9)
+    assert dec.prefill([c], [u], [N]) == 0
+    win, _, n = dec.window()
+    got = dec.peek_logits()
+    drafts = [int(t) for t in win[1:n]]
+    want_c = oracle.forward_logits(arch, w, list(c) + drafts)[-L:]
+    want_u = oracle.forward_logits(arch, w, list(u) + drafts)[-L:]
+    assert np.abs(got[0, 0] - want_c).max() < 1e-5 and np.abs(got[0, 1] - want_u).max() < 1e-5
+    assert np.abs(got[0, 0, 0] - got[0, 1, 0]).max() > 1e-3     # the two anchors really differ
+
+
+def test_random_stream_of_a_later_sequence(oracle):
+    """The counter is (step, row, SEQUENCE, 0): sequence 2 of a batch fed the same logits as sequence 0 must make
+    different draws, and its refresh draws are recomputed here with sequence index 2."""
+    cfg, arch, w, cond, uncond = _model("small_f32")
+    L, Vs, N, K, seed = 8, arch["sample_hi"] - arch["sample_lo"], 40, 60, 21
+    rng = np.random.default_rng(5)
+    one = (rng.standard_normal((1, 2, L, Vs)) * 1.0).astype(np.float32)
+    lg = np.concatenate([one, one, one], axis=0)
+    dec = oracle.Oracle(arch, w, L, cfg["prompt_len"] + N, top_k=K, reuse_tau=float("inf"), seed=seed, max_seqs=3)
+    assert dec.prefill(cond * 3, uncond * 3, [N] * 3) == 0
+    before = [dec.window(s)[0].copy() for s in range(3)]
+    res = dec.step_from_logits(lg)
+    rows = [oracle.sampling_row(one[0, 0, k], one[0, 1, k], 3.0, 1.0, K) for k in range(L)]
+    s = 2
+    for k in range(1, L):     # the initial drafts: counter (0, k, 2, 0), word 3
+        assert before[s][k] == arch["sample_lo"] + ((oracle.philox([0, k, s, 0], [seed, 0])[3] * Vs) >> 32)
+    a = 0                     # verification with word 0 of (1, k - 1, 2, 0) against the uniform reference
+    for k in range(1, L):
+        e, Z = rows[k - 1]
+        x = int(before[s][k]) - arch["sample_lo"]
+        if not oracle.accept(oracle.philox([1, k - 1, s, 0], [seed, 0])[0], oracle.weight_of(float(e[x])), Z, 1, Vs):
+            break
+        a += 1
+    assert res[s]["n_accepted"] == a
+    after, refs, n_slots = dec.window(s)
+    checked = 0
+    for k2 in range(1, n_slots):
+        k = k2 + a + 1
+        if k <= L:            # tau = inf: every later slot is redrawn from its row with words 1-2 of (1, k - 1, 2, 0)
+            e, Z = rows[k - 1]
+            words = oracle.philox([1, k - 1, s, 0], [seed, 0])
+            assert after[k2] == arch["sample_lo"] + oracle.draw(e, Z, (words[1] << 32) | words[2]) and refs[k2] == k - 1
+            checked += 1
+    assert checked > 0
+    assert not np.array_equal(before[0], before[2])
+
+
 def test_window_bookkeeping_to_the_end_of_the_image(oracle):
     """Every image token is produced exactly once, the window shrinks at the end, and the step compression
     S = tokens / steps lies in [1, L] (Sec. 5, metrics)."""

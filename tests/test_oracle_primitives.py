@@ -175,6 +175,52 @@ def test_residual_draw_exhaustive(oracle):
     assert got == [oracle.draw(ep, Zp, u << 52) for u in range(1 << 12)]
 
 
+def test_residual_draw_against_a_one_hot_reference_exhaustive(oracle):
+    """Eq. 3 with q = delta_x (a copied draft): max(0, p - q) is p with the entry of x removed (p(x) <= 1 = q(x)).
+    p = (1/2, 1/4, 1/8, 1/8): without x = 0 the tokens 1, 2, 3 come in the ratio 2 : 1 : 1; without x = 2 the tokens
+    0, 1, 3 in the ratio 4 : 2 : 1; exhaustively over 2^12 equally spaced uniforms (dyadic weights: exact counts)."""
+    ep = np.array([1.0, 0.5, 0.25, 0.25], dtype=np.float32)
+    Zp = int(oracle.weights_of(ep).sum())
+    counts = np.zeros(4, dtype=np.int64)
+    for u in range(1 << 12):
+        counts[oracle.draw_residual_onehot(ep, Zp, 0, u << 52)] += 1
+    assert list(counts) == [0, 1 << 11, 1 << 10, 1 << 10]
+    counts[:] = 0
+    for u in range(7 << 9):          # 7 * 512 cells of equal mass (residual mass 7/8 in units of 1/8), one uniform in the middle of each
+        counts[oracle.draw_residual_onehot(ep, Zp, 2, ((2 * u + 1) << 64) // (7 << 10))] += 1
+    assert list(counts) == [4 << 9, 2 << 9, 0, 1 << 9]
+    # p itself one-hot at x: the residual is empty and the draw falls back to p
+    one = np.array([0.0, 1.0, 0.0, 0.0], dtype=np.float32)
+    Z1 = int(oracle.weights_of(one).sum())
+    assert {oracle.draw_residual_onehot(one, Z1, 1, u << 52) for u in range(0, 1 << 12, 5)} == {1}
+    # ... and it agrees with the general routine fed the one-hot row
+    q = np.array([0.0, 0.0, 1.0, 0.0], dtype=np.float32)
+    Zq = int(oracle.weights_of(q).sum())
+    for u in range(0, 1 << 12, 3):
+        assert oracle.draw_residual_onehot(ep, Zp, 2, u << 52) == oracle.draw_residual(ep, Zp, q, Zq, u << 52)
+
+
+# ------------------------------------------------------- forced-token ranges
+def test_a_token_range_is_the_plain_routine_on_the_sliced_row(oracle):
+    """A forced-token mask gives ids outside [lo, hi) probability 0 before top-K: the masked row must equal the plain
+    routine run on the slice, padded with zeros; the whole range is no mask; a range of one id is one-hot."""
+    rng = np.random.default_rng(11)
+    V, K = 300, 40
+    lc = (rng.standard_normal(V) * 2).astype(np.float32)
+    lu = (rng.standard_normal(V) * 2).astype(np.float32)
+    full = oracle.sampling_row(lc, lu, 3.0, 0.9, K)
+    same = oracle.sampling_row(lc, lu, 3.0, 0.9, K, allow=(0, V))
+    assert np.array_equal(full[0], same[0]) and full[1] == same[1]
+    for lo, hi in [(0, 50), (17, 200), (250, 300), (10, 30), (120, 121)]:
+        e, Z = oracle.sampling_row(lc, lu, 3.0, 0.9, K, allow=(lo, hi))
+        e_s, Z_s = oracle.sampling_row(lc[lo:hi], lu[lo:hi], 3.0, 0.9, K)
+        assert Z == Z_s and np.array_equal(e[lo:hi], e_s)
+        assert not e[:lo].any() and not e[hi:].any()
+        assert (e > 0).sum() == min(K, hi - lo)
+    e, Z = oracle.sampling_row(lc, lu, 3.0, 0.9, K, allow=(120, 121))
+    assert e[120] == 1.0 and Z == 1 << 40
+
+
 # ---------------------------------------------------------------- accept / keep
 def test_accept_rule_against_exact_rationals(oracle):
     from fractions import Fraction
