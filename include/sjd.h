@@ -3,7 +3,7 @@
  * image-token transformer on one AMD MI355X (gfx950).  C ABI.
  *
  * The library decodes image tokens after a text prompt with the iteration of
- * Sec. 4.1 of the paper ("Speculative Jacobi Iteration"): a window of L tokens
+ * Sec. 4.1 of the paper (the speculative Jacobi iteration): a window of L tokens
  * (the last final token followed by L-1 drafts) is run through ONE causal
  * forward of the transformer against a paged KV cache, as a conditional /
  * unconditional pair for classifier-free guidance (Sec. 5.1: guidance weight,
@@ -153,7 +153,7 @@ typedef struct {
 int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd_sampling *sampling,
                void *hip_stream, sjd_ctx **out);
 
-/* Starts n_seqs decodes (Sec. 4.1: "after prefilling the text tokens").  All
+/* Starts n_seqs decodes (Sec. 4.1: the text prompt is run through the model first).  All
  * arrays are HOST arrays of length n_seqs, read during the call only.  Every
  * prompt token but the last is run through the model into the KV cache; the
  * last one becomes the first window input; the L-1 drafts are drawn uniformly.

@@ -5,7 +5,7 @@
  * computes: a pre-norm decoder-only transformer forward over a Jacobi window
  * against a flat KV cache, classifier-free guidance as a cond/uncond pair, and
  * the speculative-Jacobi verify / residual-resample / reuse rule of the paper
- * (Sec. 4.1 "Speculative Jacobi Iteration", Steps 1-4, acceptance rule,
+ * (Sec. 4.1, the speculative Jacobi iteration, Steps 1-4: acceptance rule,
  * residual distribution, confidence ratio, reuse rule; the no-reuse refinement
  * rule of Sec. 5 is the tau = +inf setting).
  *

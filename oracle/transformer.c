@@ -1,8 +1,9 @@
 /*
  * CPU oracle (test infrastructure): the decoder-only transformer forward.
  *
- * The paper (Sec. 3.1, Sec. 4.1 Step 2) only requires "one causal forward of
- * the AR model over the window after prefilling"; it gives no architecture.
+ * The paper (Sec. 3.1, Sec. 4.1 Step 2) only requires a single causal forward
+ * of the model over the window once the prompt is in the cache; it gives no
+ * architecture.
  * The architecture is the one the workload configurations name: pre-norm
  * blocks, RMSNorm, rotary position embedding on q and k (rotate-half pairing
  * (i, i + hd/2), angle pos * theta^(-2i/hd)), grouped-query attention with

@@ -147,10 +147,11 @@ SJD_D uint32_t block_max_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
 // pairs in ascending id order plus the integer normaliser.
 //
 // The K-th largest key is found exactly by narrowing a range of candidates with LDS histograms:
-//   round 0   bins in d = max - z (fp32; monotone in z), 64 per octave of d: the bulk of a row lies far below its
-//             maximum and spreads over many bins, so the histogram's atomics rarely collide.  The bin that holds the
-//             K-th largest key and the number of keys above it follow from a prefix sum over the bins; the smallest
-//             and largest key of that bin bound the candidates;
+//   round 0   bins of 2^17 consecutive keys counted down from the maximum key (order keys are the float's bits, so
+//             that is 64 bins per binade: fine where the top of a row lies, and the bulk of a row spreads over
+//             hundreds of bins, so the histogram's atomics rarely collide).  Keys more than 2047 bins away, among them
+//             every negative logit, share the last bin and are counted per wavefront.  The bin that holds the K-th
+//             largest key and the number of keys above it follow from a prefix sum over the bins;
 //   rounds 1+ 2048 equal bins over the remaining key range [lo, hi] until lo == hi (each round takes 11 bits off
 //             the range: at most three rounds).
 // Ties at the K-th value are all kept (they share a key), so nothing ever needs a tie-break.
@@ -174,6 +175,7 @@ struct SampleRowsArgs {
 };
 
 constexpr int kSelBins = 2048;
+constexpr int kBin0Shift = 17;   // round 0 of the select: 2^17 order keys per bin = 64 bins per binade of the logit
 
 // First bin (ascending index) at which the running sum of hist reaches `want` (1 <= want <= total); `before` = the
 // sum of the bins below it.  2048 bins, 1024 threads (two bins each); result in all threads.
@@ -200,32 +202,6 @@ SJD_D void find_bin(const uint32_t *hist, uint32_t want, uint32_t *wsum /* [16] 
     bin = out[0];
     before = out[1];
     __syncthreads();   // out and wsum may be reused
-}
-
-SJD_D uint32_t block_min_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-    for (int d = 32; d > 0; d >>= 1) {
-        uint32_t o = __shfl_down(v, d, 64);
-        v = o < v ? o : v;
-    }
-    __syncthreads();
-    if (lane == 0) scratch[wave] = v;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = 0xFFFFFFFFu;
-        for (int i = 0; i < nw; ++i) t = scratch[i] < t ? scratch[i] : t;
-        scratch[16] = t;
-    }
-    __syncthreads();
-    return scratch[16];
-}
-
-// bin of round 0: 64 bins per octave of d = max - z from 2^-12 up (everything nearer the maximum in bin 0,
-// everything from 2^20 on in the last bin); non-decreasing in d, hence non-increasing in z
-SJD_D int dist_bin(float m, uint32_t key) {
-    const float d = m - key_to_float(key);
-    const int b = (int)(__builtin_bit_cast(uint32_t, d) >> 17) - 115 * 64;
-    return b < 0 ? 0 : (b > kSelBins - 1 ? kSelBins - 1 : b);
 }
 
 template <int VPT>
@@ -268,7 +244,7 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
         for (int j = 0; j < kBatch; ++j) {
             const int i = i0 + j, v = tid + i * 1024;
             const uint32_t kk = order_key(guided(c[j], u[j], a.cfg_scale, a.inv_t));
-            key[i] = v >= alo && v < ahi ? kk : 0u;
+            key[i] = (uint32_t)(v - alo) < (uint32_t)(ahi - alo) ? kk : 0u;
             kmax = key[i] > kmax ? key[i] : kmax;
         }
         __builtin_amdgcn_sched_barrier(0);   // one batch of loads in flight at a time: the keys need the registers
@@ -278,26 +254,24 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
 
     uint32_t thresh = 1u;   // every candidate
     if (a.top_k < ahi - alo) {
-        // round 0: bins of the distance to the maximum
+        // round 0: bins of the key distance to the maximum, 2^17 keys each
         hist[2 * tid] = 0u;
         hist[2 * tid + 1] = 0u;
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < VPT; ++i)
-            if (key[i]) atomicAdd(&hist[dist_bin(m, key[i])], 1u);
+        for (int i = 0; i < VPT; ++i) {
+            const uint32_t b = (kmax - key[i]) >> kBin0Shift;
+            if (key[i] && b < (uint32_t)(kSelBins - 1)) atomicAdd(&hist[b], 1u);
+            // everything further away (half of a row: the negative logits) shares the last bin: one add per wavefront
+            const uint64_t far = __ballot(key[i] && b >= (uint32_t)(kSelBins - 1));
+            if (lane == 0 && far) atomicAdd(&hist[kSelBins - 1], (uint32_t)__popcll(far));
+        }
         __syncthreads();
         uint32_t bin, before;
         find_bin(hist, (uint32_t)a.top_k, wsum, sel, bin, before);
         uint32_t want = (uint32_t)a.top_k - before;   // rank of the K-th largest among the keys of that bin, from the top
-        uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i)
-            if (key[i] && dist_bin(m, key[i]) == (int)bin) {
-                lo = key[i] < lo ? key[i] : lo;
-                hi = key[i] > hi ? key[i] : hi;
-            }
-        lo = block_min_u32(lo, scratch32);
-        hi = block_max_u32(hi, scratch32);
+        uint32_t hi = kmax - (bin << kBin0Shift);     // a bin is a range of keys: (hi - 2^17, hi], the last one [1, hi]
+        uint32_t lo = bin < (uint32_t)(kSelBins - 1) && hi > (1u << kBin0Shift) ? hi - ((1u << kBin0Shift) - 1u) : 1u;
         // rounds 1+: equal bins over [lo, hi], counted from the top
         for (int round = 0; round < 4 && lo != hi; ++round) {   // block-uniform; three rounds exhaust 32 bits
             const uint32_t span = hi - lo;
@@ -353,6 +327,8 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
     // (the ballots are taken again rather than kept: VPT 64-bit masks would not fit the scalar registers; the empty
     // asm keeps the compiler from carrying them over from the counting pass)
     asm volatile("" : "+s"(thresh));
+    int tid_again = tid;   // likewise: the ids tid + 1024 i are rebuilt here, not carried in 64 registers from the loads
+    asm volatile("" : "+v"(tid_again));
     uint64_t zsum = 0;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
@@ -361,7 +337,7 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
         if (keep) {
             const uint32_t pos = base[i * 16 + wave] + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
             const float ev = exp_neg(key_to_float(key[i]) - m);
-            ids[pos] = tid + i * 1024;
+            ids[pos] = tid_again + i * 1024;
             e[pos] = ev;
             zsum += weight_of(ev);
         }
@@ -526,6 +502,7 @@ __global__ void stage_window_kernel(DecideState d, RowMap rm, int n_seqs) {
     rm.row_tok[m] = k < Le ? (k == 0 ? d.anchor[seg] : d.win_tok[s * d.L + k]) : -1;
     rm.row_pos[m] = kv + k;
     if (k == 0) { rm.seg_kv[seg] = kv; rm.seg_n[seg] = Le; }
+    if (k == 0 && (seg & 1) == 0) d.acc_len[s] = Le - 1;   // "every draft accepted" until the verification finds a rejection
 }
 
 // Rows of prefill chunk `chunk`: prompt positions chunk*L .. chunk*L + L - 1 of every segment, as far
@@ -596,33 +573,47 @@ SJD_D RowRef ref_row_of(const DecideState &d, uint32_t par_ref, int s, int rr, i
 // weight of the draft x itself under its reference (a one-hot reference sits at that very token)
 SJD_D uint64_t ref_weight_of_draft(const RowRef &q, int x) { return q.kind == 0 ? row_weight(q, x) : 1ull; }
 
-// ------------------------------------------------------------------- a11: verification (Eq. 2)
-// One block per sequence; every draft is tested in parallel, the first rejection is found with a
-// wavefront ballot per 64 drafts and a minimum across wavefronts.
-__global__ void verify_kernel(DecideState d, uint64_t seed, int row_width) {
-    const int s = blockIdx.x, L = d.L;
-    const int Le = d.Le[s];
-    if (Le == 0) return;
-    const uint32_t step = *d.step, par = step & 1u;
-    __shared__ int first_reject;
-    if (threadIdx.x == 0) first_reject = Le;
-    __syncthreads();
-    for (int base = 1; base < Le; base += blockDim.x) {
-        const int k = base + threadIdx.x;
-        bool rejected = false;
-        if (k < Le) {
-            uint32_t w[4];
-            draw_words(seed, step, (uint32_t)(k - 1), (uint32_t)s, w);
-            const int x = d.win_tok[s * L + k] - d.lo;
-            const RowRef p = step_row(d, par, s, k - 1);
-            const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k], row_width);
-            rejected = !accept_rule(w[0], row_weight(p, x), p.Z, ref_weight_of_draft(q, x), q.Z);
+// weight of id x in a stored row, looked up by a whole wavefront: every lane compares a share of the ids (independent,
+// coalesced loads in batches; a binary search would be a dozen dependent round trips to memory)
+SJD_D uint64_t wave_row_weight(const RowRef &r, int x, int lane) {
+    int hit = -1;
+    for (int i0 = 0; i0 < r.n; i0 += 64 * 8) {
+        int id[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * 64 + lane;
+            id[j] = r.ids[i < r.n ? i : r.n - 1];
         }
-        const uint64_t mask = __ballot(rejected);
-        if ((threadIdx.x & 63) == 0 && mask != 0ull) atomicMin(&first_reject, base + (threadIdx.x & ~63) + __builtin_ctzll(mask));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * 64 + lane;
+            if (i < r.n && id[j] == x) hit = i;
+        }
     }
-    __syncthreads();
-    if (threadIdx.x == 0) d.acc_len[s] = first_reject - 1;
+    const uint64_t found = __ballot(hit >= 0);
+    if (!found) return 0ull;
+    const int src = __builtin_ctzll(found);
+    const float e = hit >= 0 ? r.e[hit] : 0.0f;
+    return weight_of(__shfl(e, src, 64));
+}
+
+// ------------------------------------------------------------------- a11: verification (Eq. 2)
+// One wavefront per draft (4 per block, grid.y = sequence): all drafts are tested in parallel and the first rejection
+// is the minimum over the rejected ones.  stage_window_kernel has set acc_len[s] = Le - 1 (no rejection).
+__global__ __launch_bounds__(256) void verify_kernel(DecideState d, uint64_t seed, int row_width) {
+    const int s = blockIdx.y, L = d.L, lane = threadIdx.x & 63;
+    const int k = 1 + blockIdx.x * 4 + (threadIdx.x >> 6);   // draft in slot k against row k - 1
+    const int Le = d.Le[s];
+    if (k >= Le) return;
+    const uint32_t step = *d.step, par = step & 1u;
+    uint32_t w[4];
+    draw_words(seed, step, (uint32_t)(k - 1), (uint32_t)s, w);
+    const int x = d.win_tok[s * L + k] - d.lo;
+    const RowRef p = step_row(d, par, s, k - 1);
+    const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k], row_width);
+    const uint64_t wp = wave_row_weight(p, x, lane);
+    const uint64_t wq = q.kind == 0 ? wave_row_weight(q, x, lane) : 1ull;
+    if (lane == 0 && !accept_rule(w[0], wp, p.Z, wq, q.Z)) atomicMin(&d.acc_len[s], k - 1);
 }
 
 // ---------------------------------------------------- a12 / a13: the draws of a step (Eq. 3, Eq. 5)
@@ -644,7 +635,13 @@ SJD_D int block_inverse_cdf(F weight, int n, uint64_t u64, uint64_t *sums /* [20
     const int per = (n + nt - 1) / nt;
     const int c0 = tid * per < n ? tid * per : n, c1 = c0 + per < n ? c0 + per : n;
     uint64_t mine = 0;
-    for (int i = c0; i < c1; ++i) mine += weight(i);
+    for (int i0 = c0; i0 < c1; i0 += 8) {   // batches of 8 with clamped, unconditional evaluation: their loads go out together
+        uint64_t wv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wv[j] = weight(i0 + j < n ? i0 + j : n - 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mine += i0 + j < c1 ? wv[j] : 0ull;
+    }
     uint64_t incl = mine;
     for (int d = 1; d < 64; d <<= 1) {
         const uint64_t o = shfl_up_u64(incl, d);
@@ -669,6 +666,31 @@ SJD_D int block_inverse_cdf(F weight, int n, uint64_t u64, uint64_t *sums /* [20
     }
     __syncthreads();
     return (int)(int64_t)sums[18];
+}
+
+// A stored row that fits is copied into LDS by the whole block (one coalesced pass) and read from there afterwards:
+// the draws walk a row several times and the residual looks every kept id of p up in q, which from global memory
+// would be chains of dependent round trips.
+constexpr int kRowLdsCap = 3584;
+SJD_D void stage_row(RowRef &r, int32_t *ids_s, float *e_s) {
+    if (r.kind != 0 || r.n > kRowLdsCap) return;   // block-uniform
+    for (int i0 = threadIdx.x; i0 < r.n; i0 += 8 * blockDim.x) {   // 16 loads per thread in flight
+        int id[8];
+        float ev[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * blockDim.x, ii = i < r.n ? i : r.n - 1;
+            id[j] = r.ids[ii];
+            ev[j] = r.e[ii];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * blockDim.x;
+            if (i < r.n) { ids_s[i] = id[j]; e_s[i] = ev[j]; }
+        }
+    }
+    r.ids = ids_s;
+    r.e = e_s;
 }
 
 // token drawn from a stored row (id relative to sample_lo)
@@ -720,7 +742,9 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
         return;
     }
     const uint32_t step = *d.step, par = step & 1u;
-    extern __shared__ uint64_t sums[];
+    __shared__ uint64_t sums[20];
+    __shared__ int32_t p_ids[kRowLdsCap], q_ids[kRowLdsCap];
+    __shared__ float p_e[kRowLdsCap], q_e[kRowLdsCap];
 
     uint32_t w[4];
     draw_words(seed, step, (uint32_t)(new_slot >= 0 ? k + 1 : k), (uint32_t)s, w);
@@ -736,15 +760,20 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
             else if (code >= 0) src = step_row(d, par, s, code);
             else src = ref_row_of(d, par ^ 1u, s, code, row_width);
         }
+        stage_row(src, p_ids, p_e);
+        __syncthreads();
         const int t = draw_from_row(src, u64, sums);
         if (threadIdx.x == 0) d.cand_new[s * L + new_slot] = d.lo + t;
         return;
     }
-    const RowRef p = step_row(d, par, s, k);
+    RowRef p = step_row(d, par, s, k);
+    stage_row(p, p_ids, p_e);
 
     int tok;
     if (k == a && a < Le - 1) {
-        const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + a + 1], row_width);
+        RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + a + 1], row_width);
+        stage_row(q, q_ids, q_e);
+        __syncthreads();
         const int x = d.win_tok[s * L + a + 1] - d.lo;
         // max(0, p - q) is 0 wherever p is: the pairs of p are all there is to sum over
         auto resid = [&](int i) {
@@ -757,10 +786,13 @@ __global__ void draw_kernel(DecideState d, uint64_t seed, float tau, int rows_pe
         tok = i >= 0 ? p.ids[i] : draw_from_row(p, u64, sums);
     } else if (k > a && k <= Le - 2) {
         const int x = d.win_tok[s * L + k + 1] - d.lo;
-        const RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k + 1], row_width);
+        RowRef q = ref_row_of(d, par ^ 1u, s, d.ref_row[s * L + k + 1], row_width);
+        stage_row(q, q_ids, q_e);
+        __syncthreads();
         if (keep_rule(tau, row_weight(p, x), p.Z, ref_weight_of_draft(q, x), q.Z)) tok = x;
         else tok = draw_from_row(p, u64, sums);
     } else {
+        __syncthreads();
         tok = draw_from_row(p, u64, sums);
     }
     if (threadIdx.x == 0) d.cand[s * L + k] = d.lo + tok;
@@ -956,13 +988,13 @@ hipError_t launch_scatter_rows(hipStream_t st, const int32_t *ids, const float *
 }
 
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
-    verify_kernel<<<n_seqs, 256, 0, st>>>(d, sp.seed, sp.row_width);
+    if (d.L > 1) verify_kernel<<<dim3(ceil_div(d.L - 1, 4), n_seqs), 256, 0, st>>>(d, sp.seed, sp.row_width);
     return hipGetLastError();
 }
 
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs) {
     const int rows_per_seq = sp.init_mode >= 3 ? 2 * d.L : d.L;
-    draw_kernel<<<n_seqs * rows_per_seq, 256, 20 * sizeof(uint64_t), st>>>(d, sp.seed, sp.tau, rows_per_seq, sp.init_mode, sp.row_width);
+    draw_kernel<<<n_seqs * rows_per_seq, 256, 0, st>>>(d, sp.seed, sp.tau, rows_per_seq, sp.init_mode, sp.row_width);
     return hipGetLastError();
 }
 

@@ -1,6 +1,6 @@
 // Window attention: the L queries of a (sequence, branch) attend to the committed cache positions
-// [0, kv) and, causally, to the window positions kv .. kv + i (Sec. 4.1 Step 2: "a causal mask in the
-// attention mechanism").  Keys and values live in pages addressed through a page table.
+// [0, kv) and, causally, to the window positions kv .. kv + i (Sec. 4.1 Step 2: the parallel forward over
+// the window is causal).  Keys and values live in pages addressed through a page table.
 #pragma once
 #include "common.hip.h"
 #include "kernels_forward.hip.h"

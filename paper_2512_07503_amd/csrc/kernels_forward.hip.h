@@ -2,7 +2,7 @@
 // rotary embedding + KV page write, SwiGLU.  Each also folds in the reduction of the split-K partial
 // sums of the GEMM before it, in a fixed order (results are run-to-run deterministic).
 //
-// The paper only requires "one causal forward of the AR model over the window" (Sec. 4.1, Step 2);
+// The paper only requires a single causal forward of the model over the window (Sec. 4.1, Step 2);
 // the block structure is the one the workload shapes name.
 #pragma once
 #include "common.hip.h"
