@@ -73,6 +73,12 @@ enum {
     SJD_NO_MIXED_WIDTH = 256,  /* bf16, <= 64 rows: gate/up and head projections of more than
                                 * 256 column groups with one workgroup per group (default:
                                 * one workgroup per CU, some of them two groups wide)   */
+    SJD_KEEP_LOGITS = 1024,    /* keep the fp32 logits of every step for sjd_debug_copy_logits.  Without it the
+                                * vocabulary head of the fused bf16 path writes only the guided logits
+                                * z = (l_u + s (l_c - l_u)) / T of each position (windows of 32, or one sequence
+                                * with a window of 16), which is all the sampling stage reads            */
+    SJD_NO_HEAD_FUSION = 2048, /* the vocabulary head always writes the logits and the sampling kernel combines the
+                                * two branches (same results either way)                                 */
     SJD_NO_K_ROTATION = 512    /* bf16, row-group projection kernels: every workgroup walks K
                                 * from 0 (default: each starts at its own offset and wraps,
                                 * so that they do not all ask for the same activation lines
@@ -198,7 +204,9 @@ int sjd_set_token_ranges(sjd_ctx *ctx, int32_t seq, const int32_t *first_id, con
 const char *sjd_last_error(const sjd_ctx *ctx);
 
 /* fp32 logits of the last step, [n_seqs][2 (cond, uncond)][window][V_s],
- * V_s = sample_hi - sample_lo, to HOST memory. */
+ * V_s = sample_hi - sample_lo, to HOST memory.  SJD_ESTATE when the context does
+ * not keep them (created without SJD_KEEP_LOGITS and its head writes guided
+ * logits only). */
 int sjd_debug_copy_logits(sjd_ctx *ctx, float *dst_host);
 
 /* Runs Steps 3-4 on caller-provided logits (HOST, layout as above) instead of

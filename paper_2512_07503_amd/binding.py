@@ -10,6 +10,7 @@ _lib = None
 
 F32, BF16 = 0, 1
 KERNELS_REFERENCE, NO_GRAPH, KERNELS_ROWGROUPS, ATTENTION_CHUNKED, KERNELS_TILES, NO_L2_WARM, TILES_256_ROWS, NO_ROW_SPLIT, NO_MIXED_WIDTH, NO_K_ROTATION = 1, 2, 4, 8, 16, 32, 64, 128, 256, 512
+KEEP_LOGITS, NO_HEAD_FUSION = 1024, 2048
 OK, EINVAL, ENOMEM, ESTATE, EDEVICE, ECAPACITY = 0, -1, -2, -3, -4, -5
 
 

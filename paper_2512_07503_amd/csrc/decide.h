@@ -68,9 +68,10 @@ hipError_t launch_init_window(hipStream_t st, const DecideState &d, const Sampli
 hipError_t launch_stage_window(hipStream_t st, const DecideState &d, const RowMap &rm, int n_seqs);
 hipError_t launch_stage_prompt(hipStream_t st, const RowMap &rm, const int32_t *prompt /*[S][2][max_prompt]*/,
                                const int32_t *prompt_len, int max_prompt, int chunk, int L, int n_seqs);
-// logits: [n_seqs][2][L][V]
+// logits: [n_seqs][2][L][V]; z (may be NULL): the guided logits [n_seqs][L][V] already combined by the vocabulary head,
+// read instead of the logits
 hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, const float *logits,
-                              int n_seqs);
+                              int n_seqs, const float *z);
 hipError_t launch_verify(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 hipError_t launch_draw(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);
 hipError_t launch_commit(hipStream_t st, const DecideState &d, const SamplingParams &sp, int n_seqs);

@@ -156,6 +156,7 @@ SJD_D uint32_t block_max_u32(uint32_t v, uint32_t *scratch /* >= 17 */) {
 //             the range: at most three rounds).
 // Ties at the K-th value are all kept (they share a key), so nothing ever needs a tie-break.
 struct SampleRowsArgs {
+    const float *z_base;             // guided logits z, row (s, k) at (s * L + k) * V; NULL: computed here from the two below
     const float *lc_base, *lu_base;  // row r = (s, k): base + s * seq_stride + k * V
     long seq_stride;
     int L;                           // rows per sequence
@@ -231,19 +232,24 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
     // The loads are unconditional (index clamped to the row) and issued in batches: a load under `if (v < V)` is
     // waited for inside its branch, and a thread would pay one memory round trip per element.
     constexpr int kBatch = VPT < 16 ? VPT : 16;
+    const float *zrow = a.z_base ? a.z_base + row * V : nullptr;   // block-uniform
 #pragma unroll
     for (int i0 = 0; i0 < VPT; i0 += kBatch) {
         float c[kBatch], u[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
-            c[j] = lc[vv];
-            u[j] = lu[vv];
+            if (zrow) {
+                c[j] = zrow[vv];
+            } else {
+                c[j] = lc[vv];
+                u[j] = lu[vv];
+            }
         }
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const int i = i0 + j, v = tid + i * 1024;
-            const uint32_t kk = order_key(guided(c[j], u[j], a.cfg_scale, a.inv_t));
+            const uint32_t kk = order_key(zrow ? c[j] : guided(c[j], u[j], a.cfg_scale, a.inv_t));
             key[i] = (uint32_t)(v - alo) < (uint32_t)(ahi - alo) ? kk : 0u;
             kmax = key[i] > kmax ? key[i] : kmax;
         }
@@ -370,7 +376,8 @@ __global__ __launch_bounds__(1024) void sample_rows_wide_kernel(SampleRowsArgs a
     __shared__ uint32_t scratch32[17];
     __shared__ uint64_t scratch64[17];
     __shared__ uint32_t wcnt[16];
-    auto key_of = [&](int v) { return order_key(guided(lc[v], lu[v], a.cfg_scale, a.inv_t)); };
+    const float *zrow = a.z_base ? a.z_base + row * a.V : nullptr;
+    auto key_of = [&](int v) { return order_key(zrow ? zrow[v] : guided(lc[v], lu[v], a.cfg_scale, a.inv_t)); };
 
     uint32_t kmax = 0;
     for (int v = alo + tid; v < ahi; v += nt) {
@@ -932,8 +939,9 @@ hipError_t launch_stage_prompt(hipStream_t st, const RowMap &rm, const int32_t *
 }
 
 hipError_t launch_sample_rows(hipStream_t st, const DecideState &d, const SamplingParams &sp, const float *logits,
-                              int n_seqs) {
+                              int n_seqs, const float *z) {
     SampleRowsArgs a;
+    a.z_base = z;
     a.lc_base = logits;
     a.lu_base = logits + (long)d.L * d.V;
     a.seq_stride = 2l * d.L * d.V;
@@ -959,6 +967,7 @@ hipError_t launch_sampling_rows_plain(hipStream_t st, const float *lc, const flo
                                       uint64_t *Z, int rows, int V, const SamplingParams &sp, const int32_t *allow_lo,
                                       const int32_t *allow_hi) {
     SampleRowsArgs a;
+    a.z_base = nullptr;
     a.lc_base = lc;
     a.lu_base = lu;
     a.seq_stride = 0;

@@ -68,7 +68,15 @@ struct SkinnyArgs {
     bf16_t *h;
     int F;
     // HEAD
-    float *logits;
+    float *logits;           // [M][N] fp32 logits (NULL: not kept)
+    // HEAD with the guidance fused in (Sec. 5.1 guidance weight): rows come as a conditional tile and the
+    // unconditional tile of the same positions, and the epilogue writes z = (l_u + s (l_c - l_u)) / T per position,
+    // [positions][N], so that the sampling kernel reads one row per position and the logits need not be stored.
+    // z_mode 0: off; 1: window of 32, row tile 2 q is conditional and 2 q + 1 unconditional for sequence q;
+    // 2: one sequence, window of 16: rows 0..15 conditional, 16..31 unconditional.
+    float *z_out;
+    int z_mode;
+    float cfg_scale, inv_t;
     // PARTIAL: K split across workgroups (grid.y = ksplit), plain partial sums; the other epilogues run with ksplit 1
     int ksplit, kb_per_split;
     float *part;             // [ksplit][M][N]
@@ -130,6 +138,13 @@ SJD_D void qkv_store(const SkinnyArgs &a, const QkvRow &r, int g, int col, float
             dst[Layout<bf16_t>::v_index(0, j1, a.hd)] = float_to_bf16(v1);
         }
     }
+}
+
+// z = fma(s, l_c - l_u, l_u) / T on logits l = value * (1 / rms), every operation rounded on its own (the decision stage
+// is specified bit for bit on these values, and the compiler may otherwise contract the products into the sums)
+SJD_D float guided_z(float val_c, float inv_c, float val_u, float inv_u, float s, float inv_t) {
+    const float lc = __fmul_rn(val_c, inv_c), lu = __fmul_rn(val_u, inv_u);
+    return __fmul_rn(__fmaf_rn(s, __fsub_rn(lc, lu), lu), inv_t);
 }
 
 // One output element pair of the projection epilogues: row m, column `col` of NBW consecutive column blocks
@@ -432,6 +447,41 @@ SJD_D void skinny_body(const SkinnyArgs &a, int g, int mg, int half, int blk0) {
         }
 
     const int col = lane & 31;
+    if constexpr (EPI == EPI_HEAD) {
+        if (a.z_mode != 0) {
+            // conditional / unconditional value pairs of a position sit in the same thread: tiles j = 0 / 1 of a 64-row
+            // group (z_mode 1), or rows r / r + 16 of the one tile, i.e. hh / hh + EPT / 2 (z_mode 2)
+            auto inv_of = [&](int j, int row) {
+                float t = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) t += ssq_lds[w][j][row];
+                return 1.0f / sqrtf(t / (float)(KB * 16) + a.eps);
+            };
+            constexpr int HP = MT == 2 ? EPT : EPT / 2;   // positions per thread and column block
+#pragma unroll
+            for (int hp = 0; hp < HP; ++hp) {
+                const int v = wave + NW * hp;
+                const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int jc = 0, ju = MT == 2 ? 1 : 0, hc = hp, hu = MT == 2 ? hp : hp + EPT / 2;
+                const int row_u = MT == 2 ? row : row + 16;
+                const int mc = m_base + row, mu = MT == 2 ? m_base + 32 + row : m_base + row_u;
+                if (mu >= a.M) continue;
+                const float inv_c = inv_of(jc, row), inv_u = inv_of(ju, row_u);
+                const int pos = MT == 2 ? mg * 32 + row : row;
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int n = (blk0 + i) * 32 + col;
+                    if (n >= a.N) continue;
+                    a.z_out[(size_t)pos * a.N + n] = guided_z(out[jc][i][hc], inv_c, out[ju][i][hu], inv_u, a.cfg_scale, a.inv_t);
+                    if (a.logits) {
+                        a.logits[(size_t)mc * a.N + n] = out[jc][i][hc] * inv_c;
+                        a.logits[(size_t)mu * a.N + n] = out[ju][i][hu] * inv_u;
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < MT; ++j)
 #pragma unroll

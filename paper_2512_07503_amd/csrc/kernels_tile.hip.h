@@ -172,6 +172,38 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
         if (tid < TM) ssq_lds[tid / (32 * RT)][(tid >> 5) % RT][tid & 31] = t;
         __syncthreads();
     }
+    // Vocabulary head with the guidance fused in: a wavefront's two row tiles are the conditional and the unconditional
+    // rows of one sequence's window of 32 (256-row tiles only), so z = (l_u + s (l_c - l_u)) / T comes straight from the
+    // two accumulators of a position.
+    if constexpr (EPI == EPI_HEAD && RT == 2) {
+        if (a.z_mode == 1) {
+            const int colz = lane & 31;
+            float inv_c[16], inv_u[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                inv_c[v] = 1.0f / sqrtf(ssq_lds[wave][0][row] / (float)(KB * 16) + a.eps);
+                inv_u[v] = 1.0f / sqrtf(ssq_lds[wave][1][row] / (float)(KB * 16) + a.eps);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int n = (ct * 4 + i) * 32 + colz;
+                if (ct * 4 + i >= n_blocks || n >= a.N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const int mc = rt * TM + wave * 64 + row, mu = mc + 32;
+                    if (mu >= a.M) continue;
+                    a.z_out[((size_t)(mc >> 6) * 32 + row) * a.N + n] = guided_z(acc[0][i][v], inv_c[v], acc[1][i][v], inv_u[v], a.cfg_scale, a.inv_t);
+                    if (a.logits) {
+                        a.logits[(size_t)mc * a.N + n] = acc[0][i][v] * inv_c[v];
+                        a.logits[(size_t)mu * a.N + n] = acc[1][i][v] * inv_u[v];
+                    }
+                }
+            }
+            return;
+        }
+    }
     // The epilogue body is long; unrolled 64 times it would exceed what the compiler unrolls, and a rolled loop
     // cannot index accumulator registers.  Each lane parks one row tile x column pair (32 values) in LDS (its own
     // slots, so no barrier) and walks them in a rolled loop.

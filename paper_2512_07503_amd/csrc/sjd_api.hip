@@ -96,6 +96,9 @@ struct sjd_ctx {
     std::vector<int32_t> n_image_host;     // image tokens wanted per sequence of the current batch
     // workspaces
     float *x = nullptr, *partial = nullptr, *logits = nullptr;
+    float *z = nullptr;                    // [S][L][V_s] guided logits written by the fused vocabulary head
+    bool z_used = false;                   // the last forward's head wrote z (and the logits only if they are kept)
+    bool keep_logits = false;
     void *xn = nullptr, *q = nullptr, *attn = nullptr, *h = nullptr;
     size_t partial_elems = 0;
     RowMap rm{};
@@ -518,16 +521,28 @@ int forward_fused(sjd_ctx *c, bool with_head) {
     }
     if (with_head) {
         a.A = (const bf16_t *)c->xn; a.W = (const bf16_t *)c->lm_head; a.KB = d / 16; a.N = c->Vs;
+        // Guidance fused into the head where a position's conditional and unconditional rows meet in one thread of the
+        // epilogue: windows of 32 (row tiles alternate conditional / unconditional) and one sequence with a window of 16
+        const int groups_v = ceil_div(ceil_div(c->Vs, 32), 2);
+        const bool head_mixed = !tile && mixed_ok && skinny_mixed_applies(a, groups_v, 2, nw_for(groups_v));
+        const bool head_r2 = !tile && !head_mixed && rows2_for(groups_v);
+        int z_mode = 0;
+        if (c->z && !(md.kernel_flags & SJD_NO_HEAD_FUSION)) {
+            if (c->L == 32 && (tile || (MT == 2 && !head_r2))) z_mode = 1;
+            else if (c->L == 16 && M == 32 && !tile) z_mode = 2;
+        }
+        a.z_out = c->z; a.z_mode = z_mode; a.cfg_scale = c->sp.cfg_scale; a.inv_t = c->sp.inv_temperature;
+        a.logits = z_mode == 0 || c->keep_logits ? c->logits : nullptr;
+        c->z_used = z_mode != 0;
         if (tile) {
             whole_k();
             use_ssq();
-            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2, tile_rows));
+            SJD_LAUNCH(c, KC_GEMM_HEAD, launch_tile<EPI_HEAD>(st, a, ceil_div(c->Vs, 64) * 2, z_mode ? 256 : tile_rows));
         } else {
             whole_k();
-            const int groups_v = ceil_div(ceil_div(c->Vs, 32), 2);
-            if (mixed_ok && skinny_mixed_applies(a, groups_v, 2, nw_for(groups_v))) SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny_mixed<EPI_HEAD>(st, a, MT, groups_v));
+            if (head_mixed) SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny_mixed<EPI_HEAD>(st, a, MT, groups_v));
             else {
-                const bool r2 = rows2_for(groups_v);
+                const bool r2 = head_r2;
                 a.m_groups = r2 ? 2 * m_groups : m_groups;
                 SJD_LAUNCH(c, KC_GEMM_HEAD, launch_skinny<EPI_HEAD>(st, a, r2 ? 1 : MT, groups_v, 2, nw_for(groups_v)));
                 a.m_groups = m_groups;
@@ -675,6 +690,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
     if ((rc = dev_alloc(c, &c->h, Layout<T>::a_elems(M, F) * sizeof(T)))) return rc;
     if ((rc = dev_alloc(c, &c->q, (size_t)S * 2 * H * Layout<T>::q_elems(L, hd) * sizeof(T)))) return rc;
     if (c->fused) {
+        if ((rc = dev_alloc(c, &c->z, (size_t)S * L * c->Vs * sizeof(float)))) return rc;
         // partial tiles of K-split projections: at most 8 splits of the widest projection (2 column blocks, 2 row tiles)
         const int widest = std::max(std::max((H + 2 * Hkv) * (hd / 64), F / 32), ceil_div(c->Vs, 64));
         c->skinny_part_elems = std::max((size_t)widest * 8 * (2 * 2 * 1024 + 64), (size_t)8 * M * d);
@@ -799,8 +815,9 @@ int validate_desc(const sjd_model_desc *md, const sjd_weights *w, const sjd_samp
     return SJD_OK;
 }
 
-int run_decide(sjd_ctx *c) {
-    SJD_LAUNCH(c, KC_SAMPLE_ROWS, launch_sample_rows(c->stream, c->ds, c->sp, c->logits, c->n_seqs));
+// from_logits: the logits buffer was filled by the caller (no forward ran): the guided logits are computed from it
+int run_decide(sjd_ctx *c, bool from_logits) {
+    SJD_LAUNCH(c, KC_SAMPLE_ROWS, launch_sample_rows(c->stream, c->ds, c->sp, c->logits, c->n_seqs, c->z_used && !from_logits ? c->z : nullptr));
     SJD_LAUNCH(c, KC_VERIFY, launch_verify(c->stream, c->ds, c->sp, c->n_seqs));
     SJD_LAUNCH(c, KC_DRAW, launch_draw(c->stream, c->ds, c->sp, c->n_seqs));
     if (c->sp.init_mode == 4) SJD_LAUNCH(c, KC_COMMIT, launch_keep_rows(c->stream, c->ds, c->sp, c->n_seqs));
@@ -827,7 +844,7 @@ int enqueue_step(sjd_ctx *c) {
     SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
     int rc = forward_any(c, true);
     if (rc) return rc;
-    return run_decide(c);
+    return run_decide(c, false);
 }
 
 void drop_graph(sjd_ctx *c) {
@@ -888,6 +905,7 @@ int sjd_create(const sjd_model_desc *desc, const sjd_weights *weights, const sjd
         }
         (void)hipGetLastError();
     }
+    c->keep_logits = (desc->kernel_flags & SJD_KEEP_LOGITS) != 0;
     const bool f32 = desc->dtype == SJD_F32;
     c->use_graph = !(desc->kernel_flags & SJD_NO_GRAPH) && hip_stream != nullptr;  // the default stream cannot be captured
     c->attn_mfma = !f32 && !(desc->kernel_flags & SJD_KERNELS_REFERENCE) &&
@@ -1021,7 +1039,7 @@ int sjd_debug_step_from_logits(sjd_ctx *c, const float *logits_host, sjd_step_re
     SJD_HIP_TRY(c->err, hipMemcpyAsync(c->logits, logits_host, (size_t)c->n_seqs * 2 * c->L * c->Vs * sizeof(float),
                                        hipMemcpyHostToDevice, c->stream));
     SJD_LAUNCH(c, KC_STAGE, launch_stage_window(c->stream, c->ds, c->rm, c->n_seqs));
-    int rc = run_decide(c);
+    int rc = run_decide(c, true);
     if (rc) return rc;
     return finish_step(c, out);
 }
@@ -1029,6 +1047,10 @@ int sjd_debug_step_from_logits(sjd_ctx *c, const float *logits_host, sjd_step_re
 int sjd_debug_copy_logits(sjd_ctx *c, float *dst_host) {
     if (!c || !dst_host) return SJD_EINVAL;
     if (!c->prefilled) { sjd_set_error(c->err, "no step yet"); return SJD_ESTATE; }
+    if (c->z_used && !c->keep_logits) {
+        sjd_set_error(c->err, "the logits are not kept: this context's vocabulary head writes guided logits only (create it with SJD_KEEP_LOGITS)");
+        return SJD_ESTATE;
+    }
     SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
     SJD_HIP_TRY(c->err, hipMemcpy(dst_host, c->logits, (size_t)c->n_seqs * 2 * c->L * c->Vs * sizeof(float), hipMemcpyDeviceToHost));
     return SJD_OK;

@@ -18,8 +18,9 @@ def gpu_weights(w, dtype):
 
 def make_pair(oracle, cfg, weights=None, window=None, n_image=None, prompt_len=None, n_seqs=None, top_k=None, tau=None,
               seed=None, kernel_flags=0, kv_page_tokens=0, head_alpha=None, std=0.02, random_gains=False, n_layers=None,
-              init_mode=0, row_width=0):
-    """Returns (oracle decoder, gpu decoder, cond, uncond, n_image list) on identical inputs."""
+              init_mode=0, row_width=0, drop_logits=False):
+    """Returns (oracle decoder, gpu decoder, cond, uncond, n_image list) on identical inputs.  The GPU decoder keeps its
+    logits (the comparison protocol downloads them every step) unless drop_logits."""
     import paper_2512_07503_amd as sjd
     arch = dict(cfg["arch"])
     if n_layers is not None:
@@ -41,7 +42,8 @@ def make_pair(oracle, cfg, weights=None, window=None, n_image=None, prompt_len=N
                       reuse_tau=tau, seed=seed, max_seqs=S, init_mode=init_mode, row_width=row_width)
     g = sjd.Decoder(arch, gpu_weights(weights, cfg["dtype"]), cfg["dtype"], L, max_ctx, max_seqs=S,
                     cfg_scale=cfg["cfg_scale"], temperature=cfg["temperature"], top_k=K, reuse_tau=tau, seed=seed,
-                    kernel_flags=kernel_flags, kv_page_tokens=kv_page_tokens, init_mode=init_mode, row_width=row_width)
+                    kernel_flags=kernel_flags | (0 if drop_logits else sjd.KEEP_LOGITS), kv_page_tokens=kv_page_tokens,
+                    init_mode=init_mode, row_width=row_width)
     assert o.prefill(cond, uncond, n_img) == 0
     assert g.prefill(cond, uncond, n_img) == 0
     return o, g, cond, uncond, n_img

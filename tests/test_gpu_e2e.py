@@ -40,6 +40,8 @@ def _lockstep(o, g, S, n_steps, tol_abs=None, tol_rel=None):
 @pytest.mark.parametrize("name,flags", [("small_f32", 0), ("small_sub", 0), ("small_bf16", 0), ("small_bf16", 1),
                                         ("small_fused64", 0), ("small_fused64", 1), ("small_fused128", 0), ("small_fused128", 1),
                                         ("small_tile", 16), ("small_tile", 0), ("small_fused64", 8),
+                                        # 16384 sampled ids, window 32: the head combines the guidance branches itself
+                                        ("small_wide_vocab", 0), ("small_wide_vocab", 2048),
                                         # flags 16 + 64: 256-row workgroup tiles (the default picks 128 rows here)
                                         ("small_tile", 80),
                                         # flag 32: no extra workgroups that warm the next launch's operands into L2
@@ -179,6 +181,39 @@ def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags, wi
                                           n_image=min(cfg["n_image"], 200), kernel_flags=flags & 0xFFFF)
     worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)
     print(name, layers, "worst logits error abs/rel:", worst)
+
+
+@pytest.mark.parametrize("name,window,n_seqs,flags,fused", [
+    ("small_wide_vocab", None, None, 0, True),    # window 32, 64 rows: row tiles conditional / unconditional
+    ("small_wide_vocab", None, 2, 0, True),       # two sequences: two 64-row groups
+    ("small_fused64", None, None, 0, True),       # window 16, 32 rows: both branches in one tile
+    ("small_tile", None, None, 16, True),         # 320 rows, tile kernels
+    ("small_fused128", None, None, 0, False),     # narrow vocabulary: 32-row groups, the branches in different workgroups
+    ("small_fused64", 8, None, 0, False)])        # a window the fused head does not take
+def test_guidance_fused_into_the_head_changes_nothing(oracle, name, window, n_seqs, flags, fused):
+    """The vocabulary head that writes guided logits z per position (and no logits) against the same context keeping its
+    logits and against the head that never combines the branches: every verdict and token of a whole decode identical.
+    (The decodes that keep their logits are the ones all other tests compare with the oracle.)"""
+    import paper_2512_07503_amd as sjd
+    cfg = workload.get_config(name)
+    runs = []
+    for extra, drop in ((0, True), (0, False), (sjd.NO_HEAD_FUSION, True)):
+        o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=window, n_seqs=n_seqs, kernel_flags=flags | extra, head_alpha=6.0,
+                                              std=0.08, drop_logits=drop)
+        hist = g.decode(1000)
+        runs.append((hist, [g.tokens(s).copy() for s in range(len(n_img))]))
+        if fused and drop and not extra:
+            with pytest.raises(sjd.SjdError) as e:
+                g.logits()
+            assert e.value.code == sjd.ESTATE
+        else:
+            assert np.isfinite(g.logits()).all()
+        o.close()
+        g.close()
+    for hist, toks in runs[1:]:
+        assert hist == runs[0][0]
+        assert all(np.array_equal(a, b) for a, b in zip(toks, runs[0][1]))
+    assert all(len(t) == n for t, n in zip(runs[0][1], n_img))
 
 
 def test_error_paths_on_device(oracle):

@@ -68,7 +68,7 @@ def test_full_width_logits_against_the_oracle(oracle, capsys, name, S, n_layers,
     weights = make_weights_torch(arch, cfg["seed"], cfg["head_alpha"], "cuda", torch.bfloat16)
     cond, uncond = workload.make_prompts(arch, cfg["seed"], S, P)
     g = sjd.Decoder(arch, weights, "bf16", L, P + N, max_seqs=S, cfg_scale=cfg["cfg_scale"], temperature=cfg["temperature"],
-                    top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"])
+                    top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"], kernel_flags=sjd.KEEP_LOGITS)
     host = {k: ([t.float().cpu().numpy() for t in v] if isinstance(v, list) else v.float().cpu().numpy()) for k, v in weights.items()}
     del weights
     torch.cuda.empty_cache()

@@ -29,7 +29,7 @@ def test_full_size_step_against_the_fp32_path(name, S):
 
     def decoder(flags, dtype, w):
         d = sjd.Decoder(arch, w, dtype, L, P + N, max_seqs=S, cfg_scale=cfg["cfg_scale"], temperature=cfg["temperature"],
-                        top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"], kernel_flags=flags)
+                        top_k=cfg["top_k"], reuse_tau=cfg["tau"], seed=cfg["seed"], kernel_flags=flags | sjd.KEEP_LOGITS)
         assert d.prefill(cond, uncond, [N] * S) == 0
         return d
 

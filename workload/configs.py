@@ -52,6 +52,9 @@ TINY = {
     # 5 sequences x 2 x window 32 = 320 rows: the many-row projection kernels (tile kernels when forced by flag, else
     # row groups), with a ragged last row tile and ragged last column tiles (d = 192, F = 352, 1440 sampled ids)
     "small_tile": _cfg(_arch(2, 192, 3, 1, 352, 1500, 20, 1460), "bf16", 20, 70, 32, 150, 17, n_seqs=5),
+    # a sampled range wide enough (256 column groups) that the vocabulary head runs 64-row groups: window 32, both
+    # guidance branches of a position in one workgroup
+    "small_wide_vocab": _cfg(_arch(2, 256, 4, 2, 512, 17000, 300, 300 + 16384), "bf16", 9, 70, 32, 500, 18),
     "small_sub": _cfg(_arch(2, 64, 2, 1, 96, 700, 100, 612), "f32", 7, 30, 5, 40, 14, n_seqs=3),
 }
 
