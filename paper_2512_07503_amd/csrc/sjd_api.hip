@@ -1282,6 +1282,64 @@ int sjd_snapshot_restore(sjd_ctx *c, const void *src_host, uint64_t bytes) {
                 sjd_set_error(c->err, "snapshot corrupt (page table)");
                 return SJD_EINVAL;
             }
+    // The decoding state: the kernels index memory with these values, so every one of them is checked against the
+    // context's capacities before anything is uploaded (a buffer of the right size with wrong contents must be an
+    // error here, not an out-of-bounds access in the next step).
+    {
+        const std::vector<StateArray> arrays = state_arrays(c);
+        std::vector<const char *> at(arrays.size());
+        const char *q = r + table_n * 4 + 16;
+        for (size_t i = 0; i < arrays.size(); ++i) { at[i] = q; q += arrays[i].per_seq * n_seqs; }
+        enum { A_WIN, A_ANCHOR, A_REF, A_NIMG, A_NIMAGE, A_KV, A_LE, A_OUT, A_ACC, A_CAND, A_CANDNEW, A_IDS0, A_IDS1, A_E0, A_E1,
+               A_CNT0, A_CNT1, A_Z0, A_Z1, A_ALO, A_AHI, A_RES, A_HIDS, A_HE, A_HCNT, A_HZ };
+        auto i32 = [&](int which, size_t idx) { return ((const int32_t *)at[which])[idx]; };
+        const int L = c->L, V = c->Vs, cap = c->ds.cap, max_img = c->ds.max_img, lo = c->md.sample_lo, hi = c->md.sample_hi;
+        const int rw = c->sp.init_mode == 4 ? c->sp.row_width : 0;
+        auto bad = [&](const char *what, int s) { sjd_set_error(c->err, "snapshot corrupt (%s of sequence %d)", what, s); return SJD_EINVAL; };
+        for (int s = 0; s < n_seqs; ++s) {
+            const int n_image = i32(A_NIMAGE, s), n_img = i32(A_NIMG, s), Le = i32(A_LE, s);
+            if (n_image < 0 || n_image > max_img || n_img < 0 || n_img > n_image) return bad("token counts", s);
+            if (Le < 0 || Le > L || Le > n_image - n_img) return bad("window length", s);
+            for (int b = 0; b < 2; ++b) {
+                const int kv = i32(A_KV, (size_t)s * 2 + b);
+                if (kv < 0 || (long)kv + (n_image - n_img) > c->md.max_ctx) return bad("cache length", s);
+                // every page the rest of the decode will read or write
+                const int need = ceil_div(kv + (n_image - n_img), c->pt);
+                for (int i = 0; i < need; ++i) {
+                    const int32_t pg = table[((size_t)s * 2 + b) * c->pps + i];
+                    if (pg < 0 || pg >= c->n_pages) return bad("page table", s);
+                }
+                const int anchor = i32(A_ANCHOR, (size_t)s * 2 + b);
+                if (anchor < 0 || anchor >= c->md.vocab) return bad("window tokens", s);
+            }
+            if (i32(A_ACC, s) < -1 || i32(A_ACC, s) >= L) return bad("accept count", s);
+            for (int k = 1; k < Le; ++k) {
+                const int tok = i32(A_WIN, (size_t)s * L + k), ref = i32(A_REF, (size_t)s * L + k);
+                if (tok < lo || tok >= hi) return bad("window tokens", s);
+                if (ref >= L || ref < -2 - rw) return bad("reference rows", s);
+            }
+            for (int k = 0; k < L; ++k) {
+                const int t0 = i32(A_CAND, (size_t)s * L + k), t1 = i32(A_CANDNEW, (size_t)s * L + k);
+                if (t0 < 0 || t0 >= c->md.vocab || t1 < 0 || t1 >= c->md.vocab) return bad("drawn tokens", s);
+            }
+            for (int i = 0; i < n_image; ++i) {
+                const int a0 = i32(A_ALO, (size_t)s * max_img + i), a1 = i32(A_AHI, (size_t)s * max_img + i);
+                if (a0 < 0 || a1 > V || a0 >= a1) return bad("token ranges", s);
+            }
+            auto rows_ok = [&](int ids_arr, int cnt_arr, size_t row0, int n_rows) {
+                for (int k = 0; k < n_rows; ++k) {
+                    const int n = i32(cnt_arr, row0 + k);
+                    if (n < 0 || n > cap) return false;
+                    const int32_t *ids = (const int32_t *)at[ids_arr] + (row0 + k) * cap;
+                    for (int i = 0; i < n; ++i)
+                        if (ids[i] < 0 || ids[i] >= V || (i > 0 && ids[i] <= ids[i - 1])) return false;
+                }
+                return true;
+            };
+            if (!rows_ok(A_IDS0, A_CNT0, (size_t)s * L, L) || !rows_ok(A_IDS1, A_CNT1, (size_t)s * L, L)) return bad("stored rows", s);
+            if (rw > 0 && !rows_ok(A_HIDS, A_HCNT, (size_t)s * rw, rw)) return bad("kept rows", s);
+        }
+    }
     // everything checked: from here on the context's batch is replaced
     SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
     c->prefilled = false;
@@ -1309,6 +1367,12 @@ int sjd_snapshot_restore(sjd_ctx *c, const void *src_host, uint64_t bytes) {
     SJD_HIP_TRY(c->err, hipStreamSynchronize(c->stream));
     c->all_done = h->all_done != 0;
     c->prefilled = true;
+    {   // host copy of the image lengths (sjd_set_token_ranges checks against it)
+        const std::vector<StateArray> arrays = state_arrays(c);
+        const char *q = (const char *)src_host + snapshot_header_bytes(n_seqs) + table_n * 4 + 16;
+        for (int i = 0; i < 4; ++i) q += arrays[i].per_seq * n_seqs;
+        c->n_image_host.assign((const int32_t *)q, (const int32_t *)q + n_seqs);
+    }
     return SJD_OK;
 }
 

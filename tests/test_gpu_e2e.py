@@ -89,6 +89,18 @@ def test_decoding_modes_step_by_step(oracle, name, window, tau, top_k):
     print(name, window, tau, top_k, "steps", steps, "worst logits error abs/rel:", worst)
 
 
+@pytest.mark.parametrize("name,window", [("small_fused64", 250), ("small_fused64", 256), ("small_f32", 250)])
+def test_paper_sized_window_step_by_step(oracle, name, window):
+    """The largest window the paper uses (250, its 24 x 24-token model; Sec. 5.1) on a 320-token image: 500 rows take the
+    generic projections (not a multiple of 64), 256 the fused row groups; eight query tiles in the attention."""
+    cfg = workload.get_config(name)
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, window=window, n_image=320, head_alpha=6.0, std=0.08)
+    f32 = cfg["dtype"] == "f32"
+    worst, steps = _lockstep(o, g, 1, 400, tol_abs=1e-4 if f32 else None, tol_rel=None if f32 else 8e-2)
+    assert len(g.tokens(0)) == 320
+    print(name, window, "steps", steps, "worst logits error abs/rel:", worst)
+
+
 @pytest.mark.parametrize("name,n_seqs,window,flags", [("small_fused64", 2, None, 0), ("small_fused64", 2, None, 128),
                                                        ("small_fused64", 3, 8, 0), ("small_fused64", 4, 16, 0)])
 def test_several_sequences_in_the_row_groups(oracle, name, n_seqs, window, flags):

@@ -111,3 +111,74 @@ def test_snapshot_size_grows_with_the_accepted_prefix_and_errors_are_reported(or
     with pytest.raises(sjd.SjdError) as e:
         g2.restore(s1)
     assert e.value.code == sjd.EINVAL
+
+
+def test_restore_rejects_state_that_would_index_out_of_bounds(oracle):
+    """A buffer of the right size whose decoding state was altered (token counts, cache lengths, window tokens,
+    reference rows, page table, stored rows, token ranges) is refused with SJD_EINVAL and leaves the context usable:
+    the kernels index memory with these values.  The private layout is retraced here from the context's shape: header,
+    page table, step counter, then the per-sequence arrays in their order."""
+    import paper_2512_07503_amd as sjd
+    cfg = workload.get_config("small_fused64")
+    pt = 32
+    o, g, cond, uncond, n_img = make_pair(oracle, cfg, head_alpha=6.0, std=0.08, random_gains=True, kv_page_tokens=pt)
+    for _ in range(6):
+        g.step()
+    snap = g.snapshot()
+    arch, L, S = cfg["arch"], cfg["window"], 1
+    V = arch["sample_hi"] - arch["sample_lo"]
+    max_ctx = cfg["prompt_len"] + n_img[0]
+    pps = -(-max_ctx // pt)
+    sizes = [L * 4, 8, L * 4, 4, 4, 8, 4, max_ctx * 4, 4, L * 4, L * 4] + [L * V * 4] * 4 + [L * 4] * 2 + [L * 8] * 2 + [max_ctx * 4] * 2 + [16]
+    names = ["win", "anchor", "ref", "n_img", "n_image", "kv", "Le", "out", "acc", "cand", "cand_new", "ids0", "ids1", "e0", "e1",
+             "cnt0", "cnt1", "Z0", "Z1", "alo", "ahi", "res"]
+    kv = cfg["prompt_len"] - 1 + len(g.tokens(0))
+    hd = arch["d_model"] // arch["n_heads"]
+    page_bytes = arch["n_kv_heads"] * pt * hd * 2
+    pages = 2 * -(-kv // pt) * page_bytes * 2 * arch["n_layers"]
+    header = snap.size - (S * 2 * pps * 4 + 16 + sum(sizes) * S + pages)
+    assert 64 <= header <= 256 and header % 16 == 0, header
+    off = {"table": header}
+    at = header + S * 2 * pps * 4 + 16
+    for n, sz in zip(names, sizes):
+        off[n] = at
+        at += sz * S
+    view = snap.view(np.int32) if snap.size % 4 == 0 else None
+    assert view is not None
+    # what the retraced offsets point at must be what the context reports (else the rest of this test proves nothing)
+    toks, refs, Le = g.window(0)
+    assert view[off["n_image"] // 4] == n_img[0] and view[off["n_img"] // 4] == len(g.tokens(0)) and view[off["Le"] // 4] == Le
+    assert np.array_equal(view[off["win"] // 4 + 1: off["win"] // 4 + Le], toks[1:Le])
+    assert view[off["kv"] // 4] == kv
+
+    def refused(word, value):
+        bad = snap.copy()
+        bad.view(np.int32)[word] = value
+        with pytest.raises(sjd.SjdError) as e:
+            g.restore(bad)
+        assert e.value.code == sjd.EINVAL, (word, value)
+
+    refused(off["n_image"] // 4, 10 ** 6)
+    refused(off["n_img"] // 4, -1)
+    refused(off["n_img"] // 4, n_img[0] + 1)
+    refused(off["Le"] // 4, L + 1)
+    refused(off["kv"] // 4, 10 ** 6)
+    refused(off["kv"] // 4 + 1, -5)
+    refused(off["win"] // 4 + 1, arch["vocab"] + 7)
+    refused(off["win"] // 4 + 2, -1)
+    refused(off["ref"] // 4 + 1, L)
+    refused(off["ref"] // 4 + 1, -3)                       # a kept row, which this set-up (init_mode 0) does not have
+    refused(off["anchor"] // 4, arch["vocab"])
+    refused(off["table"] // 4 + pps - 1, 10 ** 6)         # a page the decode has not reached yet
+    refused(off["table"] // 4 + pps, -1)
+    refused(off["cnt0"] // 4, V + 1)
+    refused(off["cnt1"] // 4 + 3, -2)
+    row_with_ids = next(k for k in range(L) if view[off["cnt0"] // 4 + k] >= 2)
+    refused(off["ids0"] // 4 + row_with_ids * V, V)        # an id outside the row
+    refused(off["ids0"] // 4 + row_with_ids * V + 1, 0)    # ids not ascending
+    refused(off["alo"] // 4 + 3, V)
+    refused(off["ahi"] // 4, V + 1)
+    refused(off["acc"] // 4, L)
+    # the context is as it was: the untouched snapshot still restores and decodes on
+    g.restore(snap)
+    assert g.step() is not None
