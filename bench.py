@@ -37,23 +37,33 @@ def gemm_shapes(arch, M):
             "gemm_down": (M, d, F), "gemm_head": (M, Vs, d)}
 
 
+def head_is_fused(cfg, M):
+    """The vocabulary head combines the two guidance branches itself (one fp32 row per position instead of two) on the
+    bf16 fused path for windows of 32 and for one sequence with a window of 16."""
+    arch = cfg["arch"]
+    return cfg["dtype"] == "bf16" and (arch["d_model"] // arch["n_heads"]) % 64 == 0 and (cfg["window"] == 32 or (cfg["window"] == 16 and M == 32))
+
+
 def algorithmic_bytes(name, cfg, M, mean_ctx, sparse_rows):
     """Bytes one launch of a kernel class must move at least once (weights / KV / logits once, operands once)."""
     arch = cfg["arch"]
     esz = 4 if cfg["dtype"] == "f32" else 2
     shapes = gemm_shapes(arch, M)
+    fused = sparse_rows and head_is_fused(cfg, M)
     if name in shapes:
         m, n, k = shapes[name]
-        return n * k * esz + m * k * esz + m * n * 4
+        out_rows = m // 2 if (name == "gemm_head" and fused) else m
+        return n * k * esz + m * k * esz + out_rows * n * 4
     hd = arch["d_model"] // arch["n_heads"]
     if name == "window_attention":
         segs = M // cfg["window"]
         return 2 * mean_ctx * arch["n_kv_heads"] * hd * esz * segs
     if name == "sample_rows":
         Vs = arch["sample_hi"] - arch["sample_lo"]
-        # two logit rows in per position; out: the dense weight row, or the kept (id, weight) pairs (8 bytes each)
+        # in: two logit rows per position, or the one row of guided logits the fused head wrote; out: the dense weight
+        # row, or the kept (id, weight) pairs (8 bytes each)
         out = min(cfg["top_k"], Vs) * 8 if sparse_rows else Vs * 4
-        return (M // 2) * (Vs * 4 * 2 + out)
+        return (M // 2) * (Vs * 4 * (1 if fused else 2) + out)
     return None
 
 

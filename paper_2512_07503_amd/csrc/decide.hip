@@ -236,12 +236,17 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
 #pragma unroll
     for (int i0 = 0; i0 < VPT; i0 += kBatch) {
         float c[kBatch], u[kBatch];
+        if (zrow) {   // one uniform branch around a whole batch: a branch per load would make each wait for its data
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
-            if (zrow) {
-                c[j] = zrow[vv];
-            } else {
+            for (int j = 0; j < kBatch; ++j) {
+                const int v = tid + (i0 + j) * 1024;
+                c[j] = zrow[v < V ? v : V - 1];
+                u[j] = 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int v = tid + (i0 + j) * 1024, vv = v < V ? v : V - 1;
                 c[j] = lc[vv];
                 u[j] = lu[vv];
             }
@@ -264,14 +269,15 @@ __global__ __launch_bounds__(1024) void sample_rows_sparse_kernel(SampleRowsArgs
         hist[2 * tid] = 0u;
         hist[2 * tid + 1] = 0u;
         __syncthreads();
+        uint32_t n_far = 0;   // wave-uniform
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const uint32_t b = (kmax - key[i]) >> kBin0Shift;
             if (key[i] && b < (uint32_t)(kSelBins - 1)) atomicAdd(&hist[b], 1u);
-            // everything further away (half of a row: the negative logits) shares the last bin: one add per wavefront
-            const uint64_t far = __ballot(key[i] && b >= (uint32_t)(kSelBins - 1));
-            if (lane == 0 && far) atomicAdd(&hist[kSelBins - 1], (uint32_t)__popcll(far));
+            // everything further away (half of a row: the negative logits) shares the last bin: counted per wavefront
+            n_far += (uint32_t)__popcll(__ballot(key[i] && b >= (uint32_t)(kSelBins - 1)));
         }
+        if (lane == 0 && n_far) atomicAdd(&hist[kSelBins - 1], n_far);
         __syncthreads();
         uint32_t bin, before;
         find_bin(hist, (uint32_t)a.top_k, wsum, sel, bin, before);

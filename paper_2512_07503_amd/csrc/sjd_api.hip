@@ -68,12 +68,18 @@ struct sjd_ctx {
     // one sjd_step = the same launch sequence with the same arguments every time (what changes lives in device
     // memory): captured once per batch size into a HIP graph and replayed
     bool use_graph = false;
-    hipGraph_t graph = nullptr;
-    hipGraphExec_t graph_exec = nullptr;
-    int graph_n_seqs = 0;
+    // ... one graph per attention regime (below)
+    hipGraph_t graph[2] = {nullptr, nullptr};
+    hipGraphExec_t graph_exec[2] = {nullptr, nullptr};
+    int graph_n_seqs[2] = {0, 0};
     bool attn_mfma = false;
     int attn_chunk = 0, attn_nchunks = 0;
-    bool attn_onepass = false;             // short contexts: one workgroup per (segment, head), no merge kernel
+    // Window attention runs as one workgroup per (segment, head) while the longest context of the batch is short, and
+    // as chunks over workgroups plus a merge kernel beyond: chosen per step from the cache lengths, which the host
+    // follows from the verdicts it reads back anyway.
+    bool attn_onepass_ok = false;          // the context may use the one-pass kernel at all
+    bool attn_onepass = false;             // regime of the launches being enqueued
+    std::vector<int32_t> kv_host;          // committed cache positions per segment (sequence * 2 + branch)
     float *part_o = nullptr, *part_ml = nullptr;
     float *row_ssq = nullptr;              // [M][ceil(d / 256)] partial sums of squares of the residual stream's rows
     QkvRow *row_meta = nullptr;            // per-row tables of the fused path, rewritten by every forward
@@ -710,7 +716,7 @@ template <typename T> int alloc_buffers(sjd_ctx *c) {
         int chunk = (int)((want + 63) / 64) * 64;
         if (chunk < 128) chunk = 128;
         c->attn_chunk = chunk;
-        c->attn_onepass = !(md.kernel_flags & SJD_ATTENTION_CHUNKED) && attention_onepass_pays(md.max_ctx, hd);
+        c->attn_onepass_ok = !(md.kernel_flags & SJD_ATTENTION_CHUNKED);
         c->attn_nchunks = ceil_div(md.max_ctx, chunk);
         const size_t slots = (size_t)S * 2 * H * ceil_div(L, 32) * c->attn_nchunks;
         if ((rc = dev_alloc(c, &c->part_o, slots * 32 * hd * sizeof(float)))) return rc;
@@ -834,6 +840,8 @@ int finish_step(sjd_ctx *c, sjd_step_result *out) {
     for (int s = 0; s < c->n_seqs; ++s) {
         out[s] = c->res_host[s];
         all = all && out[s].done;
+        c->kv_host[s * 2] += out[s].n_finalized;
+        c->kv_host[s * 2 + 1] += out[s].n_finalized;
     }
     c->all_done = all;
     return SJD_OK;
@@ -847,12 +855,17 @@ int enqueue_step(sjd_ctx *c) {
     return run_decide(c, false);
 }
 
-void drop_graph(sjd_ctx *c) {
-    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
-    if (c->graph) (void)hipGraphDestroy(c->graph);
-    c->graph_exec = nullptr;
-    c->graph = nullptr;
-    c->graph_n_seqs = 0;
+void drop_graph(sjd_ctx *c, int g) {
+    if (c->graph_exec[g]) (void)hipGraphExecDestroy(c->graph_exec[g]);
+    if (c->graph[g]) (void)hipGraphDestroy(c->graph[g]);
+    c->graph_exec[g] = nullptr;
+    c->graph[g] = nullptr;
+    c->graph_n_seqs[g] = 0;
+}
+
+// one-pass attention for the coming launches iff the longest visible context (cache + rows) is short
+void choose_attention(sjd_ctx *c, int max_kv) {
+    c->attn_onepass = c->attn_mfma && c->attn_onepass_ok && attention_onepass_pays(max_kv + c->L, c->hd);
 }
 
 }  // namespace
@@ -865,7 +878,8 @@ const char *sjd_last_error(const sjd_ctx *ctx) { return ctx ? ctx->err : g_creat
 void sjd_destroy(sjd_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
-    drop_graph(c);
+    drop_graph(c, 0);
+    drop_graph(c, 1);
     for (void *p : c->allocations) (void)hipFree(p);
     if (c->res_host) (void)hipHostFree(c->res_host);
     for (hipEvent_t e : c->tracer.pool) (void)hipEventDestroy(e);
@@ -993,8 +1007,11 @@ int sjd_prefill(sjd_ctx *c, int32_t n_seqs, const int32_t *const *cond_ids, cons
     SJD_HIP_TRY(c->err, hipStreamSynchronize(st));  // the host staging vectors may go away on an early return
     c->page_table_host = table;
     c->n_image_host.assign(n_image_tokens, n_image_tokens + n_seqs);
+    c->kv_host.assign((size_t)n_seqs * 2, 0);
+    for (int s = 0; s < n_seqs; ++s) { c->kv_host[s * 2] = cond_len[s] - 1; c->kv_host[s * 2 + 1] = uncond_len[s] - 1; }
     const int chunks = ceil_div(max_prompt - 1, L);
     for (int ch = 0; ch < chunks; ++ch) {
+        choose_attention(c, ch * L);
         SJD_LAUNCH(c, KC_STAGE, launch_stage_prompt(st, c->rm, c->prompt_dev, c->prompt_len_dev, max_prompt, ch, L, n_seqs));
         int rc = forward_any(c, false);
         if (rc) return rc;
@@ -1012,20 +1029,24 @@ int sjd_step(sjd_ctx *c, sjd_step_result *out) {
     if (!out) { sjd_set_error(c->err, "null result pointer"); return SJD_EINVAL; }
     if (!c->prefilled) { sjd_set_error(c->err, "sjd_step before sjd_prefill"); return SJD_ESTATE; }
     int rc;
+    int max_kv = 0;
+    for (int32_t kv : c->kv_host) max_kv = std::max(max_kv, (int)kv);
+    choose_attention(c, max_kv);
+    const int g = c->attn_onepass ? 1 : 0;
     if (c->use_graph && !c->tracer.on) {   // per-kernel event timing needs the kernels one by one
-        if (c->graph_exec && c->graph_n_seqs != c->n_seqs) drop_graph(c);
-        if (!c->graph_exec) {
+        if (c->graph_exec[g] && c->graph_n_seqs[g] != c->n_seqs) drop_graph(c, g);
+        if (!c->graph_exec[g]) {
             SJD_HIP_TRY(c->err, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
             rc = enqueue_step(c);
-            hipGraph_t g = nullptr;
-            const hipError_t e = hipStreamEndCapture(c->stream, &g);  // always end the capture, also after a failed launch
-            if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
-            if (e != hipSuccess || !g) { sjd_set_error(c->err, "stream capture of the step failed: %s", hipGetErrorString(e)); return SJD_EDEVICE; }
-            c->graph = g;
-            SJD_HIP_TRY(c->err, hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
-            c->graph_n_seqs = c->n_seqs;
+            hipGraph_t gr = nullptr;
+            const hipError_t e = hipStreamEndCapture(c->stream, &gr);  // always end the capture, also after a failed launch
+            if (rc) { if (gr) (void)hipGraphDestroy(gr); return rc; }
+            if (e != hipSuccess || !gr) { sjd_set_error(c->err, "stream capture of the step failed: %s", hipGetErrorString(e)); return SJD_EDEVICE; }
+            c->graph[g] = gr;
+            SJD_HIP_TRY(c->err, hipGraphInstantiate(&c->graph_exec[g], c->graph[g], nullptr, nullptr, 0));
+            c->graph_n_seqs[g] = c->n_seqs;
         }
-        SJD_HIP_TRY(c->err, hipGraphLaunch(c->graph_exec, c->stream));
+        SJD_HIP_TRY(c->err, hipGraphLaunch(c->graph_exec[g], c->stream));
     } else if ((rc = enqueue_step(c))) {
         return rc;
     }
@@ -1372,6 +1393,8 @@ int sjd_snapshot_restore(sjd_ctx *c, const void *src_host, uint64_t bytes) {
         const char *q = (const char *)src_host + snapshot_header_bytes(n_seqs) + table_n * 4 + 16;
         for (int i = 0; i < 4; ++i) q += arrays[i].per_seq * n_seqs;
         c->n_image_host.assign((const int32_t *)q, (const int32_t *)q + n_seqs);
+        q += arrays[4].per_seq * n_seqs;   // the cache lengths follow the image lengths
+        c->kv_host.assign((const int32_t *)q, (const int32_t *)q + 2 * n_seqs);
     }
     return SJD_OK;
 }
