@@ -182,7 +182,8 @@ SJD_D void skinny_epilogue(const SkinnyArgs &a, int ks, int m, int blk0, int col
         for (int i = 0; i < NBW; i += 2) {
             const float gt = val[i] * inv, up = val[i + 1] * inv;
             const int n = ((blk0 + i) >> 1) * 32 + col;
-            if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(gt / (1.0f + expf(-gt)) * up);
+            // hardware exp2 and reciprocal (1 ulp each): the result is rounded to bf16 next
+            if (n < a.F) a.h[Layout<bf16_t>::a_index(m, n, a.F)] = float_to_bf16(__fdividef(gt, 1.0f + __expf(-gt)) * up);
         }
     } else {
         static_assert(EPI != EPI_QKV, "the QKV epilogue is qkv_row + qkv_rotation + qkv_store, called by the kernels");

@@ -156,11 +156,13 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
 #undef TILE_STORE_B
     }
 
+    // 1 / rms of the tile's rows, once per row (ssq_lds holds the factor, not the sum)
+    const float inv_k = 1.0f / (float)(KB * 16);
     if (kSsqLoop) {
 #pragma unroll
         for (int j = 0; j < RT; ++j) {
             const float t = ssq[j] + __shfl_xor(ssq[j], 32, 64);
-            if (lane < 32) ssq_lds[wave][j][lane] = t;
+            if (lane < 32) ssq_lds[wave][j][lane] = 1.0f / sqrtf(t * inv_k + a.eps);
         }
         __syncthreads();
     } else if (kNorm) {
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
         float t = 0.0f;
         if (tid < TM && m < a.M)
             for (int c = 0; c < a.row_ssq_n; ++c) t += a.row_ssq_part[(size_t)m * a.row_ssq_n + c];
-        if (tid < TM) ssq_lds[tid / (32 * RT)][(tid >> 5) % RT][tid & 31] = t;
+        if (tid < TM) ssq_lds[tid / (32 * RT)][(tid >> 5) % RT][tid & 31] = 1.0f / sqrtf(t * inv_k + a.eps);
         __syncthreads();
     }
     // Vocabulary head with the guidance fused in: a wavefront's two row tiles are the conditional and the unconditional
@@ -182,8 +184,8 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                inv_c[v] = 1.0f / sqrtf(ssq_lds[wave][0][row] / (float)(KB * 16) + a.eps);
-                inv_u[v] = 1.0f / sqrtf(ssq_lds[wave][1][row] / (float)(KB * 16) + a.eps);
+                inv_c[v] = ssq_lds[wave][0][row];
+                inv_u[v] = ssq_lds[wave][1][row];
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -226,29 +228,34 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) park[(i * 16 + v) * 64] = acc[j][p * 2 + i][v];
+            // four rows at a time: what the rows need from global memory (rotations, residual values) is requested
+            // for all four before the first is used
 #pragma unroll 1
-            for (int v = 0; v < 16; ++v) {
-                const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int m = rt * TM + (wave * RT + j) * 32 + row;
-                if (m >= a.M) continue;
-                float inv = 1.0f;
-                if (kNorm) inv = 1.0f / sqrtf(ssq_lds[wave][j][row] / (float)(KB * 16) + a.eps);
-                const float vals[2] = {park[v * 64], park[(16 + v) * 64]};
-                if constexpr (EPI == EPI_QKV) {
-                    const QkvRow &r = qrow[(wave * RT + j) * 32 + row];
-                    float c, sn;
-                    qkv_rotation(a, m, g, col, c, sn);
-                    qkv_store(a, r, g, col, vals[0] * inv, vals[1] * inv, c, sn);
-                } else {
-                    float xin[2] = {0.0f, 0.0f};
+            for (int v0 = 0; v0 < 16; v0 += 4) {
+                const int row0 = 2 * v0 + 4 * (lane >> 5), m0 = rt * TM + (wave * RT + j) * 32 + row0;
+                float rc[4], rs[4], xin[4][2];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    rc[u] = 1.0f;
+                    rs[u] = xin[u][0] = xin[u][1] = 0.0f;
+                    if (m0 + u >= a.M) continue;
+                    if constexpr (EPI == EPI_QKV) qkv_rotation(a, m0 + u, g, col, rc[u], rs[u]);
                     if constexpr (EPI == EPI_RESID) {
 #pragma unroll
                         for (int i = 0; i < 2; ++i) {
                             const int n = (g * 2 + i) * 32 + col;
-                            if (n < a.N) xin[i] = a.x[(size_t)m * a.N + n];
+                            if (n < a.N) xin[u][i] = a.x[(size_t)(m0 + u) * a.N + n];
                         }
                     }
-                    skinny_epilogue<EPI, 2>(a, ks, m, g * 2, col, vals, inv, xin);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int v = v0 + u, m = m0 + u;
+                    if (m >= a.M) continue;
+                    const float inv = kNorm ? ssq_lds[wave][j][row0 + u] : 1.0f;
+                    const float vals[2] = {park[v * 64], park[(16 + v) * 64]};
+                    if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[(wave * RT + j) * 32 + row0 + u], g, col, vals[0] * inv, vals[1] * inv, rc[u], rs[u]);
+                    else skinny_epilogue<EPI, 2>(a, ks, m, g * 2, col, vals, inv, xin[u]);
                 }
             }
         }
