@@ -206,12 +206,48 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
             return;
         }
     }
-    // The epilogue body is long; unrolled 64 times it would exceed what the compiler unrolls, and a rolled loop
-    // cannot index accumulator registers.  Each lane parks one row tile x column pair (32 values) in LDS (its own
-    // slots, so no barrier) and walks them in a rolled loop.
     const int col = lane & 31;
+    if constexpr (EPI != EPI_QKV) {
+        // short bodies: straight from the accumulators, four rows at a time (the residual values of all four are
+        // requested before the first is used)
+#pragma unroll
+        for (int j = 0; j < RT; ++j)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int g = ct * 2 + p;
+                if (g * 2 >= n_blocks) continue;  // past the last column pair
+#pragma unroll
+                for (int v0 = 0; v0 < 16; v0 += 4) {
+                    const int row0 = 2 * v0 + 4 * (lane >> 5), m0 = rt * TM + (wave * RT + j) * 32 + row0;
+                    float xin[4][2];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        xin[u][0] = xin[u][1] = 0.0f;
+                        if constexpr (EPI == EPI_RESID) {
+                            if (m0 + u >= a.M) continue;
+#pragma unroll
+                            for (int i = 0; i < 2; ++i) {
+                                const int n = (g * 2 + i) * 32 + col;
+                                if (n < a.N) xin[u][i] = a.x[(size_t)(m0 + u) * a.N + n];
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (m0 + u >= a.M) continue;
+                        const float inv = kNorm ? ssq_lds[wave][j][row0 + u] : 1.0f;
+                        const float vals[2] = {acc[j][p * 2][v0 + u], acc[j][p * 2 + 1][v0 + u]};
+                        skinny_epilogue<EPI, 2>(a, ks, m0 + u, g * 2, col, vals, inv, xin[u]);
+                    }
+                }
+            }
+        return;
+    }
+    // QKV: the body is long; unrolled 64 times it would exceed what the compiler unrolls, and a rolled loop cannot
+    // index accumulator registers.  Each lane parks one row tile x column pair (32 values) in LDS (its own slots, so
+    // no barrier) and walks them in a rolled loop.
     float *park = reinterpret_cast<float *>(smem) + wave * 2048 + lane;
-    // QKV: the row-dependent part of the destination (integer divisions, page lookup) once per row, not per element
+    // the row-dependent part of the destination (integer divisions, page lookup) once per row, not per element
     __shared__ QkvRow qrow[EPI == EPI_QKV ? TM : 1];
     if (EPI == EPI_QKV) {
         const int m = rt * TM + tid;
@@ -228,34 +264,23 @@ __global__ __launch_bounds__(256, RT == 2 ? 2 : 3) void gemm_tile_kernel(SkinnyA
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) park[(i * 16 + v) * 64] = acc[j][p * 2 + i][v];
-            // four rows at a time: what the rows need from global memory (rotations, residual values) is requested
-            // for all four before the first is used
+            // four rows at a time: their rotations are requested before the first is used
 #pragma unroll 1
             for (int v0 = 0; v0 < 16; v0 += 4) {
                 const int row0 = 2 * v0 + 4 * (lane >> 5), m0 = rt * TM + (wave * RT + j) * 32 + row0;
-                float rc[4], rs[4], xin[4][2];
+                float rc[4], rs[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     rc[u] = 1.0f;
-                    rs[u] = xin[u][0] = xin[u][1] = 0.0f;
-                    if (m0 + u >= a.M) continue;
-                    if constexpr (EPI == EPI_QKV) qkv_rotation(a, m0 + u, g, col, rc[u], rs[u]);
-                    if constexpr (EPI == EPI_RESID) {
-#pragma unroll
-                        for (int i = 0; i < 2; ++i) {
-                            const int n = (g * 2 + i) * 32 + col;
-                            if (n < a.N) xin[u][i] = a.x[(size_t)(m0 + u) * a.N + n];
-                        }
-                    }
+                    rs[u] = 0.0f;
+                    if (m0 + u < a.M) qkv_rotation(a, m0 + u, g, col, rc[u], rs[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int v = v0 + u, m = m0 + u;
-                    if (m >= a.M) continue;
-                    const float inv = kNorm ? ssq_lds[wave][j][row0 + u] : 1.0f;
-                    const float vals[2] = {park[v * 64], park[(16 + v) * 64]};
-                    if constexpr (EPI == EPI_QKV) qkv_store(a, qrow[(wave * RT + j) * 32 + row0 + u], g, col, vals[0] * inv, vals[1] * inv, rc[u], rs[u]);
-                    else skinny_epilogue<EPI, 2>(a, ks, m, g * 2, col, vals, inv, xin[u]);
+                    const int v = v0 + u;
+                    if (m0 + u >= a.M) continue;
+                    const float inv = ssq_lds[wave][j][row0 + u];
+                    qkv_store(a, qrow[(wave * RT + j) * 32 + row0 + u], g, col, park[v * 64] * inv, park[(16 + v) * 64] * inv, rc[u], rs[u]);
                 }
             }
         }
