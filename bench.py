@@ -37,6 +37,31 @@ def gemm_shapes(arch, M):
             "gemm_down": (M, d, F), "gemm_head": (M, Vs, d)}
 
 
+def library_gemm_us(cfg, M, repeats=30):
+    """The vendor library's bf16 GEMM (torch.matmul) at the configuration's five projection shapes: normal random
+    operands, six weight matrices in rotation so that none is served from a cache, HIP-event time per call.  Context for
+    the MFMA-bound kernels' numbers: the plain product only, none of what the path's kernels fold into theirs (RMSNorm
+    scaling, rotary embedding and KV page writes, SwiGLU, guidance), under the same power limit."""
+    import torch
+    out = {}
+    for name, (m, n, k) in gemm_shapes(cfg["arch"], M).items():
+        a = torch.randn(m, k, device="cuda", dtype=torch.bfloat16)
+        ws = [torch.randn(n, k, device="cuda", dtype=torch.bfloat16) for _ in range(6)]
+        for w in ws:
+            a @ w.t()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(repeats):
+            a @ ws[i % 6].t()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / repeats
+        out[name] = {"shape_mnk": [m, n, k], "avg_us": round(us, 2), "tflops": round(2.0 * m * n * k / us / 1e6, 1)}
+        del a, ws
+    return out
+
+
 def head_is_fused(cfg, M):
     """The vocabulary head combines the two guidance branches itself (one fp32 row per position instead of two) on the
     bf16 fused path for windows of 32 and for one sequence with a window of 16."""
@@ -317,6 +342,8 @@ def main():
     ap.add_argument("--row-width", type=int, default=0, help="tokens per image row for --init-mode 2 and 4 (default: sqrt of the image tokens)")
     ap.add_argument("--no-finish-image", action="store_true", help="do not run the image to its end for forwards/image")
     ap.add_argument("--whole-image", action="store_true", help="time every step of one image instead of --steps steps")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library's bf16 GEMM at the headline configuration's projection shapes (key library_gemm)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -386,6 +413,8 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "all_configs": all_configs,
         "setup_s": round(r["setup_s"], 1), "commit": head_commit,
     }
+    if args.library_gemm and cfg["dtype"] == "bf16":
+        out["library_gemm"] = library_gemm_us(cfg, r["M"])
     print(json.dumps(out))
 
 
