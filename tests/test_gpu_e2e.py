@@ -173,34 +173,46 @@ def test_cfg0_logits_and_decisions_every_step(oracle):
     print("cfg0 steps", steps, "worst logits error abs/rel:", worst)
 
 
-@pytest.mark.parametrize("name,layers,prompt,steps,S,flags,window", [("cfg1", 36, 24, 3, 1, 0, None), ("cfg1", 2, 120, 40, 1, 0, None),
-                                                              # norm gains drawn from U(0.5, 1.5) (flag bit 1 << 20 of this
-                                                              # table only: not a kernel flag): the fused kernels fold
-                                                              # the gain into the packed weights, one more rounding
-                                                              ("cfg1", 2, 120, 6, 1, 1 << 20, None), ("cfg2", 2, 64, 3, 1, 1 << 20, None),
-                                                              ("cfg3", 2, 64, 3, 1, 1 << 20, None), ("cfg4", 2, 64, 2, 5, 1 << 20, None),
-                                                              # gate/up and head of the 7B shapes: workgroups of two widths
-                                                              # (344 groups: 88 wide + 168; 448: 192 + 64; heads: all wide)
-                                                              ("cfg2", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 3, 1, 0, None),
-                                                              # ... with a single 32-row tile, and one group per workgroup
-                                                              ("cfg2", 2, 64, 3, 1, 0, 12), ("cfg3", 2, 64, 2, 1, 256, None),
-                                                              # 64 rows on the narrow shape: every projection as two row groups
-                                                              ("cfg1", 2, 120, 4, 1, 0, 32), ("cfg3", 2, 64, 2, 1, 128, None),
-                                                              ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None),
-                                                              # the chunk + merge attention kernels the full-length
-                                                              # 7B-class contexts use (these short twins would not)
-                                                              ("cfg1", 2, 120, 6, 1, 8, None), ("cfg3", 2, 64, 3, 1, 8, None),
-                                                              # without the L2 warm-up workgroups
-                                                              ("cfg1", 2, 120, 6, 1, 32, None), ("cfg1", 2, 120, 6, 1, 128, None),
-                                                              ("cfg1", 2, 120, 6, 1, 512, None), ("cfg2", 2, 64, 2, 1, 512, None),
-                                                              # 256-row workgroup tiles
-                                                              ("cfg4", 2, 64, 2, 5, 64, None)])
+_weights_cache = {}
+
+
+def _shape_weights(name, layers, random_gains):
+    """Weights of a benchmark shape at `layers` layers; the last set is kept, and the cases below are listed so that
+    the ones that share a set follow each other (generating a 7B-wide set takes longer than the case itself)."""
+    key = (name, layers, random_gains)
+    if key not in _weights_cache:
+        _weights_cache.clear()
+        cfg = workload.get_config(name)
+        _weights_cache[key] = workload.make_weights(dict(cfg["arch"], n_layers=layers), cfg["seed"], cfg["head_alpha"], "bf16",
+                                                    random_gains=random_gains)
+    return _weights_cache[key]
+
+
+@pytest.mark.parametrize("name,layers,prompt,steps,S,flags,window", [
+    ("cfg1", 36, 24, 3, 1, 0, None),
+    ("cfg1", 2, 120, 40, 1, 0, None),
+    # 64 rows on the narrow shape: every projection as two row groups
+    ("cfg1", 2, 120, 4, 1, 0, 32),
+    # the chunk + merge attention kernels the full-length 7B-class contexts use (these short twins would not)
+    ("cfg1", 2, 120, 6, 1, 8, None),
+    # without the L2 warm-up workgroups; one workgroup per column group; every workgroup walks K from 0
+    ("cfg1", 2, 120, 6, 1, 32, None), ("cfg1", 2, 120, 6, 1, 128, None), ("cfg1", 2, 120, 6, 1, 512, None),
+    # norm gains drawn from U(0.5, 1.5) (flag bit 1 << 20 of this table only: not a kernel flag): the fused kernels fold
+    # the gain into the packed weights, one more rounding
+    ("cfg1", 2, 120, 6, 1, 1 << 20, None), ("cfg2", 2, 64, 3, 1, 1 << 20, None),
+    ("cfg3", 2, 64, 3, 1, 1 << 20, None), ("cfg4", 2, 64, 2, 5, 1 << 20, None),
+    # gate/up and head of the 7B shapes: workgroups of two widths (344 groups: 88 wide + 168; 448: 192 + 64; heads: all
+    # wide) ... with a single 32-row tile ... every workgroup walking K from 0
+    ("cfg2", 2, 64, 3, 1, 0, None), ("cfg2", 2, 64, 3, 1, 0, 12), ("cfg2", 2, 64, 2, 1, 512, None),
+    # ... one group per workgroup; 64-row groups; chunk + merge attention
+    ("cfg3", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 2, 1, 256, None), ("cfg3", 2, 64, 2, 1, 128, None), ("cfg3", 2, 64, 3, 1, 8, None),
+    # 3 and 5 sequences on the tile kernels (192 and 320 rows); 256-row workgroup tiles
+    ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None), ("cfg4", 2, 64, 2, 5, 64, None)])
 def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags, window):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
     cfg = workload.get_config(name)
-    arch = dict(cfg["arch"], n_layers=layers)
-    w = workload.make_weights(arch, cfg["seed"], cfg["head_alpha"], "bf16", random_gains=bool(flags & (1 << 20)))
+    w = _shape_weights(name, layers, bool(flags & (1 << 20)))
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, weights=w, n_layers=layers, prompt_len=prompt, n_seqs=S, window=window,
                                           n_image=min(cfg["n_image"], 200), kernel_flags=flags & 0xFFFF)
     worst, steps = _lockstep(o, g, S, steps, tol_rel=3e-2)

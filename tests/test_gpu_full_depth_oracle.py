@@ -35,13 +35,14 @@ from helpers import assert_same_state, logits_error
 pytestmark = pytest.mark.gpu
 
 TOL = 3e-2
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _record(name, value):
-    """Keeps the measured distances beside the other run artefacts (best effort: the folder may not exist)."""
+    """Keeps the measured distances in the file that SJD_RESULTS_DIR names (nothing is written without it)."""
     try:
-        path = os.path.join(ROOT, "gpurun_out", "full_depth_vs_oracle.json")
+        if not os.environ.get("SJD_RESULTS_DIR"):
+            return
+        path = os.path.join(os.environ["SJD_RESULTS_DIR"], "full_depth_vs_oracle.json")
         table = json.load(open(path)) if os.path.exists(path) else {}
         table[name] = value
         json.dump(table, open(path, "w"), indent=1)
