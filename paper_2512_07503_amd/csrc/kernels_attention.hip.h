@@ -400,8 +400,16 @@ inline bool attention_mfma_supported(int L, int H, int Hkv, int hd, int page_tok
     return L >= 1 && (hd == 64 || hd == 128) && H / Hkv <= 4 && page_tokens % 32 == 0;
 }
 
-// One workgroup per (segment, head) pays while the keys and values of a head are a small stream for one CU.
-inline bool attention_onepass_pays(int max_tokens, int hd) { return (size_t)max_tokens * hd * 4 <= 256 * 1024; }
+// One workgroup per (segment, head), no partial results and no merge launch, against chunks of the context spread
+// over more workgroups: the single launch wins whenever its workgroups alone fill the chip (`pairs` = segments x
+// heads from half the CU count on), and otherwise while a head's keys and values are a stream of up to 1.25 MiB for
+// its CU (2 560 tokens of 128-wide heads).  Measured along whole images of the 7B shapes, per layer: 64 pairs,
+// 32 kv heads: 11.0 against 19.5 us at 300 tokens, 30.7 against 32.8 at 2 400; 64 pairs, 8 kv heads: 10.0 against
+// 22.6 at 300, 24.7 against 29.2 at 2 100, 32.4 against 30.7 at 3 100, 39.9 against 32.6 at 4 100; 512 pairs: 25.6
+// against 34.4 at 300, 119 against 141 at 2 400.
+inline bool attention_onepass_pays(int max_tokens, int hd, int pairs = 0, int n_cus = 256) {
+    return 2 * pairs >= n_cus || (size_t)max_tokens * hd * 4 <= 1280 * 1024;
+}
 
 // n_segments segments of L rows each.  onepass: contexts short enough for one workgroup per (segment, head).
 inline hipError_t launch_attention_mfma(hipStream_t st, const AttnArgs &a, int n_segments, bool onepass = false) {

@@ -74,9 +74,10 @@ struct sjd_ctx {
     int graph_n_seqs[2] = {0, 0};
     bool attn_mfma = false;
     int attn_chunk = 0, attn_nchunks = 0;
-    // Window attention runs as one workgroup per (segment, head) while the longest context of the batch is short, and
-    // as chunks over workgroups plus a merge kernel beyond: chosen per step from the cache lengths, which the host
-    // follows from the verdicts it reads back anyway.
+    // Window attention runs as one workgroup per (segment, head) while that is the faster of the two kernels (enough
+    // such workgroups to fill the chip, or a context of up to a few thousand tokens), and as chunks over workgroups
+    // plus a merge kernel beyond: chosen per step from the cache lengths, which the host follows from the verdicts
+    // it reads back anyway.
     bool attn_onepass_ok = false;          // the context may use the one-pass kernel at all
     bool attn_onepass = false;             // regime of the launches being enqueued
     std::vector<int32_t> kv_host;          // committed cache positions per segment (sequence * 2 + branch)
@@ -865,7 +866,7 @@ void drop_graph(sjd_ctx *c, int g) {
 
 // one-pass attention for the coming launches iff the longest visible context (cache + rows) is short
 void choose_attention(sjd_ctx *c, int max_kv) {
-    c->attn_onepass = c->attn_mfma && c->attn_onepass_ok && attention_onepass_pays(max_kv + c->L, c->hd);
+    c->attn_onepass = c->attn_mfma && c->attn_onepass_ok && attention_onepass_pays(max_kv + c->L, c->hd, c->n_seqs * 2 * c->md.n_heads, c->n_cus);
 }
 
 }  // namespace

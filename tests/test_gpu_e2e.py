@@ -101,11 +101,12 @@ def test_paper_sized_window_step_by_step(oracle, name, window):
     print(name, window, "steps", steps, "worst logits error abs/rel:", worst)
 
 
-@pytest.mark.parametrize("name,prompt,flags", [("small_fused128", 465, 0), ("small_fused128", 465, 2), ("small_fused64", 1000, 0)])
+@pytest.mark.parametrize("name,prompt,flags", [("small_fused128", 2510, 0), ("small_fused128", 2510, 2), ("small_fused64", 5080, 0)])
 def test_context_grows_past_the_one_workgroup_attention(oracle, name, prompt, flags):
-    """The window attention runs as one workgroup per (segment, head) while cache + window is at most 512 tokens of
-    128-wide heads (1024 of 64-wide), and split over workgroups beyond; the step picks per call.  These prompts put the
-    switch in the middle of the image: both kernels, both captured graphs, every step against the oracle."""
+    """The window attention runs as one workgroup per (segment, head) while cache + window is at most 2560 tokens of
+    128-wide heads (5120 of 64-wide; launches of few (segment, head) pairs), and split over workgroups beyond; the step
+    picks per call.  These prompts put the switch in the middle of the image: both kernels, both captured graphs,
+    every step against the oracle."""
     cfg = workload.get_config(name)
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, prompt_len=prompt, n_image=60, kernel_flags=flags, head_alpha=6.0, std=0.08)
     worst, steps = _lockstep(o, g, 1, 200, tol_rel=8e-2)
