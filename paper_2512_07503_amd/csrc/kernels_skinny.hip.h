@@ -594,25 +594,45 @@ __global__ void pack_weight_fused_kernel(const bf16_t *__restrict__ s0, const bf
     }
 }
 
-// x[m][n] += sum_ks part[ks][m][n];  xb = bf16(x) in GEMM-operand layout
-// grid (ceil(N / 256), M).  ssq_part (may be NULL): [M][gridDim.x] sums of squares of the bf16 values this block wrote.
+// x[m][n] += sum_ks part[ks][m][n];  xb = bf16(x) in GEMM-operand layout.
+// One wavefront per (row, 256 columns): a lane takes four consecutive columns (16-byte loads of the stream and of every
+// partial sum, one 8-byte store of the four bf16, which are neighbours in the operand layout), and the chunk's sum of
+// squares is a wavefront reduction: no barrier.  grid (ceil(N / 1024), M), 256 threads.
+// ssq_part (may be NULL): [M][ceil(N / 256)] sums of squares of the bf16 values written per chunk.
 __global__ __launch_bounds__(256) void resid_reduce_kernel(const float *__restrict__ part, int ksplit, int M, int N, float *__restrict__ x,
                                                            bf16_t *__restrict__ xb, float *__restrict__ ssq_part) {
-    const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+    const int m = blockIdx.y, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int n_chunks = (N + 255) >> 8, n = chunk * 256 + lane * 4;
     float sq = 0.0f;
-    if (n < N) {
+    if ((N & 3) == 0 && n + 3 < N) {
         const size_t idx = (size_t)m * N + n;
-        float v = x[idx];
-        for (int k = 0; k < ksplit; ++k) v += part[(size_t)k * M * N + idx];
-        x[idx] = v;
-        const bf16_t b = float_to_bf16(v);
-        xb[Layout<bf16_t>::a_index(m, n, N)] = b;
-        sq = bf16_to_float(b) * bf16_to_float(b);
+        float4 v = *reinterpret_cast<const float4 *>(x + idx);
+        for (int k = 0; k < ksplit; ++k) {
+            const float4 p = *reinterpret_cast<const float4 *>(part + (size_t)k * M * N + idx);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        *reinterpret_cast<float4 *>(x + idx) = v;
+        const bf16_t b0 = float_to_bf16(v.x), b1 = float_to_bf16(v.y), b2 = float_to_bf16(v.z), b3 = float_to_bf16(v.w);
+        uint2 packed;
+        packed.x = (uint32_t)b0 | ((uint32_t)b1 << 16);
+        packed.y = (uint32_t)b2 | ((uint32_t)b3 << 16);
+        *reinterpret_cast<uint2 *>(xb + Layout<bf16_t>::a_index(m, n, N)) = packed;   // n % 4 == 0: one 8-element group
+        const float f0 = bf16_to_float(b0), f1 = bf16_to_float(b1), f2 = bf16_to_float(b2), f3 = bf16_to_float(b3);
+        sq = (f0 * f0 + f1 * f1) + (f2 * f2 + f3 * f3);
+    } else {
+        for (int nn = n; nn < n + 4 && nn < N; ++nn) {
+            const size_t idx = (size_t)m * N + nn;
+            float v = x[idx];
+            for (int k = 0; k < ksplit; ++k) v += part[(size_t)k * M * N + idx];
+            x[idx] = v;
+            const bf16_t b = float_to_bf16(v);
+            xb[Layout<bf16_t>::a_index(m, nn, N)] = b;
+            sq += bf16_to_float(b) * bf16_to_float(b);
+        }
     }
     if (ssq_part) {
-        __shared__ float scratch[17];
-        const float t = block_sum_f32(sq, scratch);
-        if (threadIdx.x == 0) ssq_part[(size_t)m * gridDim.x + blockIdx.x] = t;
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+        if (lane == 0 && chunk < n_chunks) ssq_part[(size_t)m * n_chunks + chunk] = sq;
     }
 }
 

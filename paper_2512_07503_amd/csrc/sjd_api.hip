@@ -435,7 +435,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks, tile_rows));
             const int ksplit = a.ksplit;
             SJD_LAUNCH(c, KC_ADDNORM, after([&] {
-                           resid_reduce_kernel<<<dim3(ceil_div(d, 256), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
+                           resid_reduce_kernel<<<dim3(ceil_div(d, 1024), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
                        }));
             ssq_ready = true;
             return SJD_OK;
@@ -467,7 +467,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         SJD_LAUNCH(c, cls, launch_skinny<EPI_PARTIAL>(st, a, MT, groups, nbw_d, nw_for(groups * a.ksplit)));
         const int ksplit = a.ksplit;
         SJD_LAUNCH(c, KC_ADDNORM, after([&] {
-                       resid_reduce_kernel<<<dim3(ceil_div(d, 256), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
+                       resid_reduce_kernel<<<dim3(ceil_div(d, 1024), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
                    }));
         return SJD_OK;
     };
