@@ -18,6 +18,14 @@
 // (2, 3) of a tile are rotary / gate-up pairs.  RMSNorm row sums of squares come from the kernel that wrote the
 // rows (partial sums per row, added in a fixed order by the epilogue) when it provides them, else from the
 // activation fragments as they are consumed - which costs a third of the loop's issue slots.
+//
+// What bounds it (measured): replaying only the loop's global loads takes 80 % of the kernel's time whatever the
+// depth of the ring - all workgroups of an XCD ask its L2 for the same few lines at the same time (a k-step's
+// activation fragments; every weight line once per row tile), which it serves at under half the rate it reaches on
+// scattered reads - and under sustained MFMA load the shader clock settles near 1.7-1.9 GHz.  More k-steps per
+// barrier, deeper rings, LDS reads a stage ahead, a fifth wavefront requesting lines ahead and eight wavefronts per
+// tile all measured within 1 % or worse; fewer operand bytes per MFMA would need larger tiles than 512 rows on 256
+// CUs leave room for.
 #pragma once
 #include "kernels_skinny.hip.h"
 
