@@ -37,14 +37,23 @@ def _same(a, b):
             assert np.array_equal(x, y)
 
 
-@pytest.mark.parametrize("name,init_mode,row_width,clobber", [("small_f32", 0, 0, "steps"), ("small_fused64", 0, 0, "steps"),
-                                                              ("small_fused64", 4, 6, "prefill"), ("small_sub", 3, 0, "prefill"),
-                                                              ("small_tile", 0, 0, "steps")])
-def test_restore_replays_the_steps_after_the_save(oracle, name, init_mode, row_width, clobber):
+@pytest.mark.parametrize("name,init_mode,row_width,clobber,ranges", [
+    ("small_f32", 0, 0, "steps", False), ("small_fused64", 0, 0, "steps", False), ("small_fused64", 4, 6, "prefill", False),
+    ("small_sub", 3, 0, "prefill", False), ("small_tile", 0, 0, "steps", False),
+    # forced-token ranges are part of the state: the batch that takes the context over in between resets them
+    ("small_fused64", 0, 0, "prefill", True), ("small_sub", 0, 0, "prefill", True)])
+def test_restore_replays_the_steps_after_the_save(oracle, name, init_mode, row_width, clobber, ranges):
     cfg = workload.get_config(name)
     S = cfg["n_seqs"]
     o, g, cond, uncond, n_img = make_pair(oracle, cfg, head_alpha=6.0, std=0.08, random_gains=True, init_mode=init_mode,
                                           row_width=row_width, kernel_flags=16 if name == "small_tile" else 0)
+    if ranges:
+        lo0, hi0 = cfg["arch"]["sample_lo"], cfg["arch"]["sample_hi"]
+        for q in range(S):
+            n = n_img[q]
+            first = np.array([lo0 + 2 + q if (i + 1) % 5 == 0 else lo0 + 3 * q for i in range(n)], dtype=np.int32)
+            end = np.array([lo0 + 3 + q if (i + 1) % 5 == 0 else hi0 - 7 * q for i in range(n)], dtype=np.int32)
+            assert o.set_token_ranges(q, first, end) == 0 and g.set_token_ranges(q, first, end) == 0
     before = []
     _run(o, g, S, 4, before)
     snap = g.snapshot()
