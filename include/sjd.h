@@ -70,9 +70,13 @@ enum {
                                 * with one workgroup per group (default: two, 16 rows each);
                                 * more rows: 64-row groups also for projections of so few
                                 * column groups that 32-row groups would each get a CU     */
-    SJD_NO_MIXED_WIDTH = 256,  /* bf16, <= 64 rows: gate/up and head projections of more than
-                                * 256 column groups with one workgroup per group (default:
-                                * one workgroup per CU, some of them two groups wide)   */
+    SJD_NO_MIXED_WIDTH = 256,  /* bf16: no launch mixes workgroup shapes.  <= 64 rows: gate/up and
+                                * head projections of more than 256 column groups with one
+                                * workgroup per group (default: one workgroup per CU, some of
+                                * them two groups wide); >= 256 rows: one tile height per launch
+                                * (default: 256-row tiles on every CU with the remaining column
+                                * tiles as 128-row tiles beside them, where the 256-row tiles
+                                * number between one and two per CU)                    */
     SJD_KEEP_LOGITS = 1024,    /* keep the fp32 logits of every step for sjd_debug_copy_logits.  Without it the
                                 * vocabulary head of the fused bf16 path writes only the guided logits
                                 * z = (l_u + s (l_c - l_u)) / T of each position (windows of 32, or one sequence

@@ -330,7 +330,7 @@ inline int tile_rows_for(int M, int n_blocks, int ksplit, int n_cus) {
 
 // n_blocks = packed 32-column blocks of W.  The K range of a workgroup is a.kb_per_split k-blocks (grid.y = a.ksplit).
 template <int EPI>
-inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks, int tile_rows = 0) {
+inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks, int tile_rows = 0, bool two_heights = true) {
     const int tile_rows_in = tile_rows;   // 0: the launcher chooses
     if (a.M <= 0 || n_blocks <= 0 || a.KB <= 0 || a.ksplit < 1 || (size_t)a.kb_per_split * a.ksplit < (size_t)a.KB) return hipErrorInvalidValue;
     if (EPI != EPI_PARTIAL && a.ksplit != 1) return hipErrorInvalidValue;
@@ -343,8 +343,10 @@ inline hipError_t launch_tile(hipStream_t st, const SkinnyArgs &a, int n_blocks,
     // beside them (measured at 512 x 22016 x 4096: 95.5 us against 108.0 with 128-row tiles and 126 with 256-row tiles)
     const int n_cus = a.n_cus > 0 ? a.n_cus : 256;
     const int rt2 = (a.M + 255) / 256, rt1 = (a.M + 127) / 128;
-    if (tile_rows_in == 0 && EPI != EPI_HEAD && a.ksplit == 1 && rt1 > rt2 && col_tiles * rt2 > n_cus && col_tiles * rt2 < 2 * n_cus &&
-        n_cus / rt2 >= 8) {
+    // (not where 128-row tiles alone give every CU the same number of workgroups: 1024 x 12288 x 4096, three per CU,
+    // 120.6 us against 132.7 mixed)
+    if (two_heights && tile_rows_in == 0 && EPI != EPI_HEAD && a.ksplit == 1 && rt1 > rt2 && col_tiles * rt2 > n_cus && col_tiles * rt2 < 2 * n_cus &&
+        n_cus / rt2 >= 8 && (col_tiles * rt1) % n_cus != 0) {
         const int ct_split = n_cus / rt2 / 8 * 8;
         const int wg_split = ct_split * rt2, wg_rest = 8 * ((col_tiles - ct_split + 7) / 8) * rt1;
         if (ssq_loop) gemm_tile_mixed_kernel<EPI, true><<<dim3(wg_split + wg_rest, 1), 256, 0, st>>>(a, n_blocks, row_tiles32, col_tiles, ct_split, wg_split, rt2, rt1);

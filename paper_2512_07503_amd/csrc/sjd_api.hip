@@ -427,12 +427,12 @@ int forward_fused(sjd_ctx *c, bool with_head) {
             a.kb_per_split = ceil_div(a.KB, ks);
             a.ksplit = ceil_div(a.KB, a.kb_per_split);
             if (a.ksplit == 1) {
-                SJD_LAUNCH(c, cls, launch_tile<EPI_RESID>(st, a, n_blocks, tile_rows));
+                SJD_LAUNCH(c, cls, launch_tile<EPI_RESID>(st, a, n_blocks, tile_rows, mixed_ok));
                 ssq_ready = false;
                 return SJD_OK;
             }
             if ((size_t)a.ksplit * M * d > c->skinny_part_elems) return no_room();
-            SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks, tile_rows));
+            SJD_LAUNCH(c, cls, launch_tile<EPI_PARTIAL>(st, a, n_blocks, tile_rows, mixed_ok));
             const int ksplit = a.ksplit;
             SJD_LAUNCH(c, KC_ADDNORM, after([&] {
                            resid_reduce_kernel<<<dim3(ceil_div(d, 1024), M), 256, 0, st>>>(c->skinny_part, ksplit, M, d, c->x, (bf16_t *)c->xn, ssq_out);
@@ -484,7 +484,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         if (tile) {
             whole_k();
             use_ssq();
-            SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2, tile_rows));
+            SJD_LAUNCH(c, KC_GEMM_QKV, launch_tile<EPI_QKV>(st, a, (H + 2 * Hkv) * (hd / 64) * 2, tile_rows, mixed_ok));
         } else {
             whole_k();
             a.row_split = row_split_for(groups_qkv);
@@ -504,7 +504,7 @@ int forward_fused(sjd_ctx *c, bool with_head) {
         if (tile) {
             whole_k();
             use_ssq();
-            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2, tile_rows));
+            SJD_LAUNCH(c, KC_GEMM_GATEUP, launch_tile<EPI_SWIGLU>(st, a, F / 32 * 2, tile_rows, mixed_ok));
         } else {
             whole_k();
             a.row_split = row_split_for(F / 32);

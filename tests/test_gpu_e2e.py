@@ -207,8 +207,9 @@ def _shape_weights(name, layers, random_gains):
     ("cfg2", 2, 64, 3, 1, 0, None), ("cfg2", 2, 64, 3, 1, 0, 12), ("cfg2", 2, 64, 2, 1, 512, None),
     # ... one group per workgroup; 64-row groups; chunk + merge attention
     ("cfg3", 2, 64, 3, 1, 0, None), ("cfg3", 2, 64, 2, 1, 256, None), ("cfg3", 2, 64, 2, 1, 128, None), ("cfg3", 2, 64, 3, 1, 8, None),
-    # 3 and 5 sequences on the tile kernels (192 and 320 rows); 256-row workgroup tiles
-    ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None), ("cfg4", 2, 64, 2, 5, 64, None)])
+    # 3 and 5 sequences on the tile kernels (192 and 320 rows; at 320 the gate/up launch mixes 256-row and 128-row
+    # tiles); 256-row workgroup tiles only; one tile height per launch
+    ("cfg4", 2, 64, 3, 3, 0, None), ("cfg4", 2, 64, 2, 5, 0, None), ("cfg4", 2, 64, 2, 5, 64, None), ("cfg4", 2, 64, 2, 5, 256, None)])
 def test_benchmark_shapes_bf16(oracle, name, layers, prompt, steps, S, flags, window):
     """The benchmark shapes: full depth at short context for configs[1]; the 7B-class widths, heads, GQA, vocabulary
     sub-range and batch on depth-reduced twins (a full-depth fp64 CPU forward of those takes hours)."""
